@@ -1,0 +1,132 @@
+"""Throughput of the ViT-Huge 32-layer encoder forward (one pipeline stage that
+holds the whole model) at micro-batch 64 on one MI355X.
+
+A step is one ep_stage_forward over one synthetic micro-batch already resident
+in HBM.  Prints ONE JSON line: images/s, the roofline of the dominant kernel
+(the first MLP GEMM, timed with HIP events inside the library on the stream it
+runs on), the per-kernel time split of a layer, and the CPU checker timed on
+the host cores on a bounded sample (one image through all 32 layers).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--model", default="vit_huge", help="vit_huge (headline) | vit_large | vit_base")
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--layers", type=int, default=0, help="0 = all layers of the model")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-split", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (a pipeline stage is one device's work); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2110_14895_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    binding.lib()          # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+
+    sh = synth.SHAPES[args.model]
+    n_layers = args.layers or sh.n_layers
+    B = args.batch
+    layers = [synth.layer_params(sh, l, bf16=True) for l in range(n_layers)]
+    x = synth.activations(sh, B, bf16=True)
+    cfg = binding.VitConfig(sh.n_layers, sh.d_model, sh.n_heads, sh.d_mlp, sh.n_tokens, sh.ln_eps,
+                            binding.EP_BF16, binding.EP_BF16, binding.EP_F32)
+    stage = binding.Stage(cfg, 0, n_layers, [synth.as_param_dtype(p, True) for p in layers], B)
+    xin = torch.from_numpy(synth.f32_to_bf16_bits(x).reshape(x.shape).view(np.int16)).cuda()
+    out = torch.empty(x.shape, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        stage.forward(xin, B, out, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        stage.forward(xin, B, out, stream)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    ms_per_step = dt / args.steps * 1e3
+    images_per_s = B * args.steps / dt
+    flops_per_step = B * n_layers * sh.flops_per_image_per_layer()
+    tflops = flops_per_step / (dt / args.steps) / 1e12
+
+    # ---- dominant kernel: FC1 (+GELU) GEMM, events around each of its launches in a second
+    # pass over the same steps
+    R = B * sh.n_tokens
+    roofline = None
+    kernels = {}
+    ids = range(len(binding.KERNEL_NAMES)) if not args.no_kernel_split else [5]
+    for kid in ids:
+        steps = args.steps if kid == 5 else min(args.steps, 3)
+        stage.trace_begin(kid, n_layers * steps)
+        for _ in range(steps):
+            stage.forward(xin, B, out, stream)
+        torch.cuda.synchronize()
+        n, sec = stage.trace_end()
+        kernels[binding.KERNEL_NAMES[kid]] = sec / n * 1e6 if n else None
+        if kid == 5 and n:
+            fl = 2.0 * R * sh.d_model * sh.d_mlp
+            achieved = fl / (sec / n) / 1e12
+            roofline = {"kernel": "fc1_gelu_gemm", "bound": "mfma", "achieved": round(achieved, 2),
+                        "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": None,
+                        "avg_us": round(sec / n * 1e6, 2), "launches": n,
+                        "flop_per_launch": fl}
+
+    result = {
+        "metric": "images/sec + % bf16 MFMA peak, ViT-Huge 32-layer encoder fwd, 1 MI355X",
+        "value": round(images_per_s, 2), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{sh.name} {n_layers}-layer stage, micro-batch {B}, T={sh.n_tokens}, "
+                               f"D={sh.d_model}, H={sh.n_heads}, M={sh.d_mlp}; bf16 in, fp32 residual and output",
+                   "micro_batch": B, "layers": n_layers},
+        "tflops": round(tflops, 2), "frac_bf16_mfma_peak": round(tflops / PEAK_BF16_MFMA_TFLOPS, 4),
+        "roofline": roofline,
+        "kernel_us_per_launch": {k: (round(v, 2) if v else None) for k, v in kernels.items()},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        ocfg = oracle.OracleConfig(sh.d_model, sh.n_heads, sh.d_mlp, sh.n_tokens, sh.ln_eps)
+        t0 = time.perf_counter()
+        ref = oracle.stage_forward(ocfg, layers, x[:1])
+        cdt = time.perf_counter() - t0
+        got = out[:1].cpu().numpy().astype(np.float64)
+        err = float(np.abs(got - ref).max() / np.sqrt((ref * ref).mean()))
+        result["cpu_baseline"] = {"value": round(1.0 / cdt, 4), "unit": "images/s",
+                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": f"1 image of the same micro-batch through all {n_layers} layers "
+                                            f"({cdt:.1f} s of float64 CPU work)"}
+        result["parity_image0_max_abs_over_rms"] = round(err, 5)
+
+    print(json.dumps(result))
+    stage.destroy()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

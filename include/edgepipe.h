@@ -1,0 +1,204 @@
+/*
+ * edgepipe.h - C ABI of the MI355X pipeline-stage library.
+ *
+ * The library runs the forward pass of one pipeline stage of a partitioned
+ * transformer encoder on one GPU, and plans the partition on the CPU.
+ *
+ *   - A model with L layers is cut into k parts T_1..T_k of consecutive layers;
+ *     part T_i is one pipeline stage on one device and the model is the
+ *     composition T_k(...T_2(T_1(X))) applied to one micro-batch X
+ *     (paper section 3.1).  ep_stage_create / ep_stage_forward are one T_i.
+ *   - A layer is multi-head self-attention, an MLP, two layer normalisations
+ *     and residual connections (paper section 2.1, "Transformer-based Models").
+ *   - Which layers go to which device is the partition problem of sections
+ *     3.2-3.3 (Eq. 1-3, Algorithm 1): ep_partition.
+ *   - The per-layer execution times the planner needs are measured on the
+ *     device (section 5.1, per-layer execution time figure): ep_stage_profile.
+ *
+ * Conventions
+ *   - All functions return an ep_status and never throw or abort; the text of
+ *     the last error of the calling thread is ep_last_error().
+ *   - "host" / "device" on a pointer says where the memory lives.  The library
+ *     never takes ownership of a caller buffer.
+ *   - A stage handle is not thread-safe; distinct handles are independent.
+ *   - One GPU: the device current at ep_stage_create is the stage's device.
+ */
+#ifndef EDGEPIPE_H
+#define EDGEPIPE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ep_stage ep_stage_t; /* opaque, created and destroyed by the library */
+
+typedef enum {
+    EP_OK = 0,
+    EP_ERR_INVALID_ARG = 1, /* null pointer, bad range, B > max_batch, ... */
+    EP_ERR_UNSUPPORTED = 2, /* shape or dtype combination the kernels do not cover */
+    EP_ERR_OOM = 3,         /* host or device allocation failed */
+    EP_ERR_HIP = 4,         /* a HIP runtime call failed; see ep_last_error() */
+    EP_ERR_INFEASIBLE = 5   /* ep_partition: no strategy satisfies the memory limits */
+} ep_status;
+
+typedef enum { EP_F32 = 0, EP_BF16 = 1 } ep_dtype;
+
+/*
+ * Encoder configuration.  Shapes of one layer: width D = d_model, H = n_heads
+ * heads of d_head = D / H, MLP width M = d_mlp, T = n_tokens tokens per image
+ * (patches plus the class token).  n_layers is L of the whole model; a stage
+ * covers a sub-range of it.
+ *
+ * param_dtype selects the arithmetic path:
+ *   EP_F32  - fp32 operands and accumulation everywhere; in_dtype and
+ *             out_dtype must be EP_F32.
+ *   EP_BF16 - parameters are bf16; GEMM and attention operands are bf16 on the
+ *             matrix cores with fp32 accumulation; LayerNorm statistics,
+ *             softmax, and the residual stream are fp32.  in_dtype / out_dtype
+ *             choose bf16 or fp32 for the stage input / output (fp32 output
+ *             keeps the residual stream un-rounded across stage boundaries).
+ *             Requires D % 64 == 0, M % 64 == 0, d_head in {64, 80},
+ *             T <= 288.
+ */
+typedef struct {
+    int32_t n_layers;    /* L */
+    int32_t d_model;     /* D */
+    int32_t n_heads;     /* H */
+    int32_t d_mlp;       /* M */
+    int32_t n_tokens;    /* T */
+    float ln_eps;        /* added to the variance inside the square root */
+    int32_t param_dtype; /* ep_dtype of every pointer in ep_layer_weights */
+    int32_t in_dtype;    /* ep_dtype of x_in */
+    int32_t out_dtype;   /* ep_dtype of x_out */
+} ep_vit_config;
+
+/*
+ * Parameters of one layer, HOST pointers, element type param_dtype (bf16 is
+ * the upper 16 bits of an IEEE float32).  Dense weights are [out, in]
+ * row-major, y = x W^T + b:
+ *   ln1_g, ln1_b [D]     LayerNorm before attention (gain, shift)
+ *   w_qkv [3D, D], b_qkv [3D]   fused projection; rows 0..D-1 produce q,
+ *                        D..2D-1 k, 2D..3D-1 v; inside each block row h*d_head+e
+ *                        is component e of head h
+ *   w_o [D, D], b_o [D]  attention output projection
+ *   ln2_g, ln2_b [D]     LayerNorm before the MLP
+ *   w_fc1 [M, D], b_fc1 [M]     first dense layer, followed by exact (erf) GELU
+ *   w_fc2 [D, M], b_fc2 [D]     second dense layer
+ */
+typedef struct {
+    const void *ln1_g, *ln1_b, *w_qkv, *b_qkv, *w_o, *b_o;
+    const void *ln2_g, *ln2_b, *w_fc1, *b_fc1, *w_fc2, *b_fc2;
+} ep_layer_weights;
+
+/*
+ * Build the stage T_i that holds layers layer_begin .. layer_end-1 of the model
+ * (section 3.1).  `layers` has layer_end - layer_begin entries of host pointers;
+ * the parameters are copied to the current device (the caller may free its
+ * buffers afterwards).  A workspace for micro-batches of up to max_batch images
+ * is allocated here; nothing is allocated later.  On success *out is the handle.
+ * Errors: INVALID_ARG (null, empty or out-of-range layer range, max_batch < 1),
+ * UNSUPPORTED (see ep_vit_config), OOM, HIP.
+ */
+ep_status ep_stage_create(const ep_vit_config *cfg, int32_t layer_begin, int32_t layer_end,
+                          const ep_layer_weights *layers, int32_t max_batch, ep_stage_t **out);
+
+/*
+ * Y = T_i(X) for one micro-batch (section 3.1).  x_in and x_out are DEVICE
+ * buffers [B, T, D] row-major (D contiguous) of in_dtype / out_dtype; they may
+ * be the same buffer when the two dtypes have the same size.  For each layer of
+ * the stage, with x the fp32 residual stream (section 2.1):
+ *   x <- x + W_o . MHSA(LN1(x)) + b_o
+ *   x <- x + W_2 . gelu(W_1 . LN2(x) + b_1) + b_2
+ * MHSA: per head, softmax over all T tokens of q.k / sqrt(d_head), no mask.
+ * All work is enqueued on `stream` (a hipStream_t; NULL is the default stream);
+ * the call does not allocate and does not synchronise.  1 <= B <= max_batch.
+ */
+ep_status ep_stage_forward(ep_stage_t *stage, const void *x_in, int32_t B, void *x_out,
+                           void *stream);
+
+/*
+ * Measure the execution time of each layer of the stage at micro-batch B on this
+ * device: the T_comp(l, u) input of the planner (section 3.3; section 5.1
+ * measures the same quantity per layer).  Each layer is run `iters` times
+ * (after one untimed run) on the stage's own workspace, timed with events on
+ * `stream`; per_layer_seconds (HOST, one double per layer of the stage) gets the
+ * mean.  Synchronises `stream`.
+ */
+ep_status ep_stage_profile(ep_stage_t *stage, int32_t B, int32_t iters, void *stream,
+                           double *per_layer_seconds);
+
+/*
+ * Per-kernel timing of the forward pass.  The kernels of one layer, in launch
+ * order (section 2.1's parts of a layer):
+ */
+typedef enum {
+    EP_K_LN1 = 0,  /* LayerNorm before attention */
+    EP_K_QKV = 1,  /* fused q|k|v projection */
+    EP_K_ATTN = 2, /* multi-head softmax attention */
+    EP_K_PROJ = 3, /* output projection + residual */
+    EP_K_LN2 = 4,  /* LayerNorm before the MLP */
+    EP_K_FC1 = 5,  /* first dense layer + GELU */
+    EP_K_FC2 = 6,  /* second dense layer + residual */
+    EP_K_COUNT = 7
+} ep_kernel_id;
+
+/*
+ * Start timing one kernel of the layer: until ep_stage_trace_end, every launch
+ * of `kernel` made by ep_stage_forward on this stage is bracketed by a pair of
+ * events recorded on the forward's stream (at most max_launches pairs, created
+ * here; later launches run untimed).  Tracing one kernel at a time keeps the
+ * other kernels' launches back to back.
+ */
+ep_status ep_stage_trace_begin(ep_stage_t *stage, int32_t kernel, int32_t max_launches);
+/*
+ * Stop timing: waits for the recorded events, writes the number of timed
+ * launches and the sum of their durations in seconds (HOST), frees the events.
+ */
+ep_status ep_stage_trace_end(ep_stage_t *stage, int32_t *launches, double *seconds);
+
+/* Device bytes held by the stage (parameters + workspace). */
+ep_status ep_stage_device_bytes(const ep_stage_t *stage, uint64_t *bytes);
+
+/* Free the stage's device memory.  The caller must have synchronised any stream
+ * that still runs its work.  NULL is allowed. */
+void ep_stage_destroy(ep_stage_t *stage);
+
+/*
+ * Heterogeneity-aware optimal partition (sections 3.2-3.3), CPU only,
+ * deterministic, no global state.
+ *
+ * Inputs (HOST):
+ *   L layers, D devices (1 <= D <= 20).
+ *   t_comp[l*D + u]   seconds to run layer l on device u; T_comp of a run of
+ *                     layers is their sum, added first layer to last.
+ *   layer_mem[l]      M_j, memory a layer needs;  dev_mem[u]  m_u, capacity.
+ *   xfer_bytes[l]     P_j, bytes sent to the next stage when a stage ends with
+ *                     layer l.
+ *   bw[u*D + v]       b_{u,v}, bytes/s from device u to device v.
+ * A strategy selects S <= D distinct devices in pipeline order and gives each a
+ * run of consecutive layers whose memory fits.  A stage's period is
+ * max(T_comp, P_j / b_{u,v}) (Eq. 1, Eq. 2); the last stage sends nothing.
+ * T_opt is the smallest achievable largest period (Eq. 3).
+ *
+ * Outputs (HOST): *t_opt; *n_stages = S; for stage s < S: stage_dev[s],
+ * stage_first[s], stage_last[s] (0-based, inclusive); the three arrays must
+ * have room for D entries.  Among all strategies that reach T_opt the one
+ * returned has the lexicographically smallest sequence
+ * (dev_0, last_0, dev_1, last_1, ...), so the answer is unique.
+ * Errors: INVALID_ARG, OOM, INFEASIBLE (outputs untouched).
+ */
+ep_status ep_partition(int32_t L, int32_t D, const double *t_comp, const double *layer_mem,
+                       const double *dev_mem, const double *xfer_bytes, const double *bw,
+                       double *t_opt, int32_t *n_stages, int32_t *stage_dev,
+                       int32_t *stage_first, int32_t *stage_last);
+
+const char *ep_status_string(ep_status s);
+/* Text of the calling thread's most recent error ("" if none). */
+const char *ep_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EDGEPIPE_H */

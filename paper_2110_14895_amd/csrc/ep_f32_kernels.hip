@@ -1,0 +1,215 @@
+// fp32 path of a ViT encoder layer (paper section 2.1): plain-ALU kernels used
+// for small fp32 configurations where exactness matters more than speed.
+// LayerNorm: one wavefront per row.  GEMM: 64x64 LDS tiles, 4x4 outputs per
+// thread.  Attention: one workgroup per (image, head, query), scores in LDS.
+#include "ep_kernels.h"
+
+namespace {
+
+constexpr int WAVE = 64;
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
+    return v;
+}
+
+__device__ inline float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, WAVE));
+    return v;
+}
+
+__device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
+
+// ---------------------------------------------------------------- LayerNorm
+__global__ __launch_bounds__(256) void ln_f32_kernel(const float *__restrict__ x,
+                                                     const float *__restrict__ g,
+                                                     const float *__restrict__ b, float eps,
+                                                     float *__restrict__ y, int64_t rows, int D)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int64_t row = (int64_t)blockIdx.x * (blockDim.x / WAVE) + (threadIdx.x / WAVE);
+    if (row >= rows) return;
+    const float *xr = x + row * D;
+    float s = 0.f;
+    for (int d = lane; d < D; d += WAVE) s += xr[d];
+    const float mean = wave_sum(s) / (float)D;
+    float v = 0.f;
+    for (int d = lane; d < D; d += WAVE) {
+        const float c = xr[d] - mean;
+        v += c * c;
+    }
+    const float inv = 1.0f / sqrtf(wave_sum(v) / (float)D + eps);
+    float *yr = y + row * D;
+    for (int d = lane; d < D; d += WAVE) yr[d] = (xr[d] - mean) * inv * g[d] + b[d];
+}
+
+// --------------------------------------------------------------------- GEMM
+constexpr int GT = 64;  // tile edge
+constexpr int GK = 16;  // k step
+
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__ A,
+                                                       const float *__restrict__ W,
+                                                       const float *__restrict__ bias,
+                                                       const float *resid, float *C, int64_t M,
+                                                       int N, int K)
+{
+    __shared__ float As[GK][GT + 1];
+    __shared__ float Ws[GK][GT + 1];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int64_t m0 = (int64_t)blockIdx.y * GT;
+    const int n0 = blockIdx.x * GT;
+    float acc[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += GK) {
+        // 64 rows x 16 k per operand = 1024 elements, 4 per thread
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int id = threadIdx.x + i * 256;
+            const int r = id >> 4, k = id & 15;
+            const int64_t gm = m0 + r;
+            const int gn = n0 + r;
+            As[k][r] = (gm < M && k0 + k < K) ? A[gm * K + k0 + k] : 0.f;
+            Ws[k][r] = (gn < N && k0 + k < K) ? W[(int64_t)gn * K + k0 + k] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < GK; ++k) {
+            float a[4], w[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = Ws[k][tx * 4 + j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t gm = m0 + ty * 4 + i;
+        if (gm >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int gn = n0 + tx * 4 + j;
+            if (gn >= N) continue;
+            float v = acc[i][j] + bias[gn];
+            if (EPI == EPI_BIAS_GELU) v = gelu_erf(v);
+            if (EPI == EPI_BIAS_RESID) v += resid[gm * N + gn];
+            C[gm * N + gn] = v;
+        }
+    }
+}
+
+// ---------------------------------------------------------------- attention
+// One workgroup (128 threads) per (image, head, query token).
+__global__ __launch_bounds__(128) void attn_f32_kernel(const float *__restrict__ qkv,
+                                                       float *__restrict__ o, int T, int D, int H)
+{
+    extern __shared__ float sm[];  // [T] scores, then [dh] query, then 2 partials
+    const int dh = D / H;
+    float *sc = sm;
+    float *qs = sm + T;
+    float *part = qs + dh;
+    const int t = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const float *base = qkv + (int64_t)b * T * 3 * D;
+    for (int e = tid; e < dh; e += 128) qs[e] = base[(int64_t)t * 3 * D + h * dh + e];
+    __syncthreads();
+    const float scale = 1.0f / sqrtf((float)dh);
+    float mx = -INFINITY;
+    for (int u = tid; u < T; u += 128) {
+        const float *k = base + (int64_t)u * 3 * D + D + h * dh;
+        float acc = 0.f;
+        for (int e = 0; e < dh; ++e) acc = fmaf(qs[e], k[e], acc);
+        acc *= scale;
+        sc[u] = acc;
+        mx = fmaxf(mx, acc);
+    }
+    mx = wave_max(mx);
+    if (lane == 0) part[wv] = mx;
+    __syncthreads();
+    mx = fmaxf(part[0], part[1]);
+    __syncthreads();
+    float sum = 0.f;
+    for (int u = tid; u < T; u += 128) {
+        const float p = expf(sc[u] - mx);
+        sc[u] = p;
+        sum += p;
+    }
+    sum = wave_sum(sum);
+    if (lane == 0) part[wv] = sum;
+    __syncthreads();
+    const float inv = 1.0f / (part[0] + part[1]);
+    for (int e = tid; e < dh; e += 128) {
+        float acc = 0.f;
+        for (int u = 0; u < T; ++u) acc = fmaf(sc[u], base[(int64_t)u * 3 * D + 2 * D + h * dh + e], acc);
+        o[((int64_t)b * T + t) * D + h * dh + e] = acc * inv;
+    }
+}
+
+__global__ void fill_pattern_kernel(float *x, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint32_t v = (uint32_t)i * 2654435761u;
+    v ^= v >> 15;
+    v *= 2246822519u;
+    v ^= v >> 13;
+    x[i] = (float)(int32_t)v * (1.0f / 2147483648.0f);
+}
+
+}  // namespace
+
+hipError_t ep_f32_layernorm(const float *x, const float *g, const float *b, float eps, float *y,
+                            int64_t rows, int D, hipStream_t s)
+{
+    if (rows <= 0) return hipSuccess;
+    const int rows_per_block = 256 / WAVE;
+    const unsigned grid = (unsigned)((rows + rows_per_block - 1) / rows_per_block);
+    hipLaunchKernelGGL(ln_f32_kernel, dim3(grid), dim3(256), 0, s, x, g, b, eps, y, rows, D);
+    return hipGetLastError();
+}
+
+hipError_t ep_f32_gemm(const float *A, const float *W, const float *bias, const float *resid,
+                       float *C, int64_t M, int N, int K, int epi, hipStream_t s)
+{
+    if (M <= 0 || N <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((N + GT - 1) / GT), (unsigned)((M + GT - 1) / GT));
+    if (grid.y > 65535u) return hipErrorInvalidValue;
+    switch (epi) {
+    case EPI_BIAS:
+        hipLaunchKernelGGL(gemm_f32_kernel<EPI_BIAS>, grid, dim3(256), 0, s, A, W, bias, resid, C, M, N, K);
+        break;
+    case EPI_BIAS_GELU:
+        hipLaunchKernelGGL(gemm_f32_kernel<EPI_BIAS_GELU>, grid, dim3(256), 0, s, A, W, bias, resid, C, M, N, K);
+        break;
+    case EPI_BIAS_RESID:
+        hipLaunchKernelGGL(gemm_f32_kernel<EPI_BIAS_RESID>, grid, dim3(256), 0, s, A, W, bias, resid, C, M, N, K);
+        break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t ep_f32_attention(const float *qkv, float *o, int B, int T, int D, int H, hipStream_t s)
+{
+    if (B <= 0) return hipSuccess;
+    if (H > 65535 || B > 65535) return hipErrorInvalidValue;
+    const size_t smem = sizeof(float) * (size_t)(T + D / H + 2);
+    if (smem > 64 * 1024) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(attn_f32_kernel, dim3(T, H, B), dim3(128), smem, s, qkv, o, T, D, H);
+    return hipGetLastError();
+}
+
+hipError_t ep_fill_pattern(float *x, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_pattern_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, n);
+    return hipGetLastError();
+}

@@ -1,0 +1,45 @@
+// Launchers of the stage's HIP kernels (gfx950).  Every launcher enqueues on the
+// given stream, allocates nothing and returns the launch status.  Shapes are
+// validated by the caller (ep_stage.hip); the launchers re-check the
+// divisibility assumptions their kernels make and refuse otherwise.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+// GEMM epilogues: C = A . W^T + bias, then ...
+enum EpEpilogue {
+    EPI_BIAS = 0,       // store (bf16 on the bf16 path, fp32 on the fp32 path)
+    EPI_BIAS_GELU = 1,  // exact erf GELU, store
+    EPI_BIAS_RESID = 2  // add the fp32 residual, store fp32 (out may alias resid)
+};
+
+// ---- fp32 path -------------------------------------------------------------
+hipError_t ep_f32_layernorm(const float *x, const float *g, const float *b, float eps, float *y,
+                            int64_t rows, int D, hipStream_t s);
+hipError_t ep_f32_gemm(const float *A, const float *W, const float *bias, const float *resid,
+                       float *C, int64_t M, int N, int K, int epi, hipStream_t s);
+hipError_t ep_f32_attention(const float *qkv, float *o, int B, int T, int D, int H, hipStream_t s);
+
+// ---- bf16 path -------------------------------------------------------------
+// x fp32 [rows, D] -> y bf16, fp32 statistics
+hipError_t ep_bf16_layernorm(const float *x, const float *g, const float *b, float eps,
+                             uint16_t *y, int64_t rows, int D, hipStream_t s);
+hipError_t ep_bf16_to_f32(const uint16_t *in, float *out, int64_t n, hipStream_t s);
+hipError_t ep_f32_to_bf16(const float *in, uint16_t *out, int64_t n, hipStream_t s);
+// A bf16 [M, K], W bf16 [N, K]; out bf16 (EPI_BIAS, EPI_BIAS_GELU) or fp32 (EPI_BIAS_RESID)
+hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias,
+                        const float *resid, void *C, int64_t M, int N, int K, int epi,
+                        hipStream_t s);
+// qkv bf16 [B*T, 3D] -> o bf16 [B*T, D]
+hipError_t ep_bf16_attention(const uint16_t *qkv, uint16_t *o, int B, int T, int D, int H,
+                             hipStream_t s);
+bool ep_bf16_attention_supported(int T, int d_head);
+
+// deterministic fill used by the profiler (values in [-1, 1])
+hipError_t ep_fill_pattern(float *x, int64_t n, hipStream_t s);
+
+// tile-configuration sweep hooks of the bf16 GEMM (0 <= cfg < ep_bf16_gemm_num_configs())
+int ep_bf16_gemm_num_configs();
+hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, const float *bias,
+                               const float *resid, void *C, int64_t M, int N, int K, int epi,
+                               hipStream_t s);

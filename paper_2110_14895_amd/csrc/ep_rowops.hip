@@ -1,0 +1,153 @@
+// HBM-bound row kernels of the bf16 path: LayerNorm over the fp32 residual
+// stream producing the bf16 GEMM operand (paper section 2.1: the two layer
+// normalisations of a layer), and dtype conversion at the stage boundary.
+//
+// LayerNorm: one wavefront per row, the whole row held in registers (float4
+// loads, D <= 64*4*MAXV), mean then centred variance (two passes over
+// registers, one pass over memory), fp32 statistics, round-to-nearest-even
+// narrowing.  Algorithmic traffic per row: 4*D bytes read, 2*D written.
+#include "ep_kernels.h"
+
+namespace {
+
+constexpr int WAVE = 64;
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
+    return v;
+}
+
+__device__ inline uint32_t pack_bf16x2(float lo, float hi)
+{
+    const __bf16 a = (__bf16)lo, b = (__bf16)hi;   // fptrunc: round to nearest even
+    return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+}
+
+// NV = number of float4 per lane (D = 256 * NV exactly, or ragged when GUARD)
+template <int NV, bool GUARD>
+__global__ __launch_bounds__(256) void ln_bf16_kernel(const float *__restrict__ x,
+                                                      const float *__restrict__ g,
+                                                      const float *__restrict__ b, float eps,
+                                                      uint16_t *__restrict__ y, int64_t rows, int D)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int64_t row = (int64_t)blockIdx.x * (blockDim.x / WAVE) + (threadIdx.x / WAVE);
+    if (row >= rows) return;
+    const float4 *xr = reinterpret_cast<const float4 *>(x + row * D);
+    const int nvec = D >> 2;
+    float4 v[NV];
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + i * WAVE;
+        if (!GUARD || c < nvec) {
+            v[i] = xr[c];
+            s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+        } else {
+            v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    const float mean = wave_sum(s) / (float)D;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + i * WAVE;
+        if (!GUARD || c < nvec) {
+            v[i].x -= mean; v[i].y -= mean; v[i].z -= mean; v[i].w -= mean;
+            q += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
+        }
+    }
+    const float inv = 1.0f / sqrtf(wave_sum(q) / (float)D + eps);
+    const float4 *g4 = reinterpret_cast<const float4 *>(g);
+    const float4 *b4 = reinterpret_cast<const float4 *>(b);
+    uint2 *yr = reinterpret_cast<uint2 *>(y + row * D);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = lane + i * WAVE;
+        if (!GUARD || c < nvec) {
+            const float4 gg = g4[c], bb = b4[c];
+            uint2 o;
+            o.x = pack_bf16x2(v[i].x * inv * gg.x + bb.x, v[i].y * inv * gg.y + bb.y);
+            o.y = pack_bf16x2(v[i].z * inv * gg.z + bb.z, v[i].w * inv * gg.w + bb.w);
+            yr[c] = o;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void bf16_to_f32_kernel(const uint16_t *__restrict__ in,
+                                                          float *__restrict__ out, int64_t n4)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n4) return;
+    const uint2 p = reinterpret_cast<const uint2 *>(in)[i];
+    float4 o;
+    o.x = __uint_as_float(p.x << 16);
+    o.y = __uint_as_float(p.x & 0xFFFF0000u);
+    o.z = __uint_as_float(p.y << 16);
+    o.w = __uint_as_float(p.y & 0xFFFF0000u);
+    reinterpret_cast<float4 *>(out)[i] = o;
+}
+
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float *__restrict__ in,
+                                                          uint16_t *__restrict__ out, int64_t n4)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n4) return;
+    const float4 v = reinterpret_cast<const float4 *>(in)[i];
+    uint2 o;
+    o.x = pack_bf16x2(v.x, v.y);
+    o.y = pack_bf16x2(v.z, v.w);
+    reinterpret_cast<uint2 *>(out)[i] = o;
+}
+
+template <int NV>
+hipError_t launch_ln(const float *x, const float *g, const float *b, float eps, uint16_t *y,
+                     int64_t rows, int D, hipStream_t s)
+{
+    const unsigned grid = (unsigned)((rows + 3) / 4);
+    if (D == NV * 256)
+        hipLaunchKernelGGL((ln_bf16_kernel<NV, false>), dim3(grid), dim3(256), 0, s, x, g, b, eps, y, rows, D);
+    else
+        hipLaunchKernelGGL((ln_bf16_kernel<NV, true>), dim3(grid), dim3(256), 0, s, x, g, b, eps, y, rows, D);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t ep_bf16_layernorm(const float *x, const float *g, const float *b, float eps,
+                             uint16_t *y, int64_t rows, int D, hipStream_t s)
+{
+    if (rows <= 0) return hipSuccess;
+    if (D % 4 != 0 || D <= 0 || D > 8 * 256) return hipErrorInvalidValue;
+    const int nv = (D + 255) / 256;
+    switch (nv) {
+    case 1: return launch_ln<1>(x, g, b, eps, y, rows, D, s);
+    case 2: return launch_ln<2>(x, g, b, eps, y, rows, D, s);
+    case 3: return launch_ln<3>(x, g, b, eps, y, rows, D, s);
+    case 4: return launch_ln<4>(x, g, b, eps, y, rows, D, s);
+    case 5: return launch_ln<5>(x, g, b, eps, y, rows, D, s);
+    case 6: return launch_ln<6>(x, g, b, eps, y, rows, D, s);
+    case 7: return launch_ln<7>(x, g, b, eps, y, rows, D, s);
+    default: return launch_ln<8>(x, g, b, eps, y, rows, D, s);
+    }
+}
+
+hipError_t ep_bf16_to_f32(const uint16_t *in, float *out, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    if (n % 4) return hipErrorInvalidValue;
+    const int64_t n4 = n / 4;
+    hipLaunchKernelGGL(bf16_to_f32_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, in, out, n4);
+    return hipGetLastError();
+}
+
+hipError_t ep_f32_to_bf16(const float *in, uint16_t *out, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    if (n % 4) return hipErrorInvalidValue;
+    const int64_t n4 = n / 4;
+    hipLaunchKernelGGL(f32_to_bf16_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, in, out, n4);
+    return hipGetLastError();
+}

@@ -316,3 +316,17 @@ def heterogeneous_cluster(layer_cost_s: np.ndarray, shape: VitShape, batch: int,
     bw = np.repeat((bw_mbps * 1e6 / 8.0)[:, None], D, axis=1)
     return PartitionInstance(np.ascontiguousarray(t_comp), layer_mem, dev_mem, xfer,
                              np.ascontiguousarray(bw))
+
+
+def as_param_dtype(params: Dict[str, np.ndarray], bf16: bool) -> Dict[str, np.ndarray]:
+    """Host arrays in the storage type a stage is created from: bf16 bit
+    patterns (uint16; the values must already be bf16-representable) or float32."""
+    if not bf16:
+        return {k: np.ascontiguousarray(v, dtype=np.float32) for k, v in params.items()}
+    out = {}
+    for k, v in params.items():
+        bits = f32_to_bf16_bits(v)
+        if not np.array_equal(bf16_bits_to_f32(bits).reshape(np.shape(v)), np.asarray(v, dtype=np.float32)):
+            raise ValueError(f"{k} holds values that are not bf16-representable")
+        out[k] = bits.reshape(np.shape(v))
+    return out

@@ -1,0 +1,205 @@
+"""GPU parity: ep_stage_forward through the C ABI against the float64 CPU
+checker on the same seeded host buffers.  Tolerances: max-abs error over the
+RMS of the reference <= 1e-4 on the fp32 path and <= 2e-2 on the bf16 path."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2110_14895_amd import binding, synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def layers_of(sh, n, *, bf16, affine=True, w_std=0.02, first=0):
+    return [synth.layer_params(sh, first + l, bf16=bf16, randomize_affine=affine, w_std=w_std)
+            for l in range(n)]
+
+
+# ------------------------------------------------------------------ fp32 path
+def test_tiny_fp32_config():
+    # D=192, 3 heads of 64, MLP 768, T=65, 2 layers, batch 1, weights N(0, 0.02), biases 0
+    sh = synth.SHAPES["tiny"]
+    layers = layers_of(sh, 2, bf16=False, affine=False)
+    x = synth.activations(sh, 1)
+    st = H.make_stage(sh, layers, 0, 2, 1, bf16=False)
+    got = H.run_stage(st, x)
+    ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x)
+    assert H.rel_err(got, ref) <= H.TOL_F32
+
+
+@pytest.mark.parametrize("T,D,Hh,M,B", [(7, 24, 3, 40, 3), (65, 192, 3, 768, 2), (130, 72, 2, 100, 1)])
+def test_fp32_ragged_shapes_with_affine_and_bias(T, D, Hh, M, B):
+    sh = synth.custom_shape(f"f32_{T}_{D}", 2, D, Hh, M, T)
+    layers = layers_of(sh, 2, bf16=False, w_std=0.1)
+    x = synth.activations(sh, B)
+    st = H.make_stage(sh, layers, 0, 2, B + 1, bf16=False)
+    got = H.run_stage(st, x)
+    ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x)
+    assert H.rel_err(got, ref) <= H.TOL_F32
+
+
+# ------------------------------------------------------------------ bf16 path
+def _zero(layers, names):
+    out = []
+    for p in layers:
+        q = dict(p)
+        for n in names:
+            q[n] = np.zeros_like(q[n])
+        out.append(q)
+    return out
+
+
+SMALL_BF16 = [
+    # T, D, H, M, B : d_head 64 / 80, tokens spanning 3 / 7 / 9 key tiles, ragged row counts
+    (65, 128, 2, 256, 3),
+    (197, 256, 4, 512, 2),
+    (257, 320, 4, 640, 2),
+    (33, 128, 2, 192, 5),
+    (1, 128, 2, 128, 1),
+    (288, 128, 2, 256, 1),
+]
+
+
+@pytest.mark.parametrize("T,D,Hh,M,B", SMALL_BF16)
+@pytest.mark.parametrize("part", ["mlp_only", "attention_only", "full"])
+def test_bf16_small_shapes(T, D, Hh, M, B, part):
+    sh = synth.custom_shape(f"bf_{T}_{D}_{Hh}", 2, D, Hh, M, T)
+    layers = layers_of(sh, 2, bf16=True, w_std=0.05)
+    if part == "mlp_only":
+        layers = _zero(layers, ["w_o", "b_o"])
+    elif part == "attention_only":
+        layers = _zero(layers, ["w_fc2", "b_fc2"])
+    x = synth.activations(sh, B, bf16=True)
+    st = H.make_stage(sh, layers, 0, 2, B, bf16=True)
+    got = H.run_stage(st, x)
+    ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x)
+    ref_r = oracle.stage_forward(H.oracle_cfg(sh, round_mode=1), layers, x)
+    e, er = H.rel_err(got, ref), H.rel_err(got, ref_r)
+    print(f"{part} T={T} D={D}: err {e:.3e}, vs operand-rounded reference {er:.3e}")
+    assert e <= H.TOL_BF16
+    assert er <= 1e-2          # agreement with the operand-rounded reference is much closer
+
+
+def test_bf16_zero_output_weights_is_exact_identity():
+    sh = synth.custom_shape("bf_id", 2, 128, 2, 256, 65)
+    layers = _zero(layers_of(sh, 2, bf16=True), ["w_o", "b_o", "w_fc2", "b_fc2"])
+    x = synth.activations(sh, 2, bf16=True)
+    st = H.make_stage(sh, layers, 0, 2, 2, bf16=True)
+    np.testing.assert_array_equal(H.run_stage(st, x), x)
+
+
+def test_bf16_io_dtypes_and_batch_smaller_than_max():
+    sh = synth.custom_shape("bf_io", 1, 128, 2, 256, 65)
+    layers = layers_of(sh, 1, bf16=True, w_std=0.05)
+    x = synth.activations(sh, 3, bf16=True)
+    ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x)
+    base = H.run_stage(H.make_stage(sh, layers, 0, 1, 8, bf16=True), x)
+    assert H.rel_err(base, ref) <= H.TOL_BF16
+    f32_in = H.run_stage(H.make_stage(sh, layers, 0, 1, 8, bf16=True, in_bf16=False), x)
+    np.testing.assert_array_equal(f32_in, base)         # same values in, same kernels
+    bf_out = H.run_stage(H.make_stage(sh, layers, 0, 1, 8, bf16=True, out_bf16=True), x)
+    np.testing.assert_array_equal(bf_out, synth.round_to_bf16(base).reshape(base.shape))
+
+
+def test_batch_limits_and_in_place():
+    import torch
+    sh = synth.custom_shape("bf_lim", 1, 128, 2, 256, 65)
+    layers = layers_of(sh, 1, bf16=True)
+    st = H.make_stage(sh, layers, 0, 1, 2, bf16=True, in_bf16=False)
+    x = synth.activations(sh, 2, bf16=True)
+    want = H.run_stage(st, x)
+    buf = torch.from_numpy(x).cuda()
+    st.forward(buf, 2, buf)                              # x_out aliases x_in
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(buf.cpu().numpy(), want)
+    with pytest.raises(binding.EdgePipeError) as ei:
+        st.forward(buf, 3, buf)
+    assert ei.value.status == binding.EP_ERR_INVALID_ARG
+    with pytest.raises(binding.EdgePipeError):
+        st.forward(buf, 0, buf)
+
+
+def test_stage_composition_and_caller_stream():
+    # T_2(T_1(X)) on two stage handles equals the single stage over both ranges (section 3.1)
+    import torch
+    sh = synth.custom_shape("bf_comp", 4, 128, 2, 256, 65)
+    layers = layers_of(sh, 4, bf16=True, w_std=0.05)
+    x = synth.activations(sh, 3, bf16=True)
+    whole = H.make_stage(sh, layers, 0, 4, 3, bf16=True)
+    s1 = H.make_stage(sh, layers[:1], 0, 1, 3, bf16=True)
+    s2 = H.make_stage(sh, layers[1:], 1, 4, 3, bf16=True, in_bf16=False)
+    stream = torch.cuda.Stream()
+    ref = H.run_stage(whole, x)
+    mid = H.run_stage(s1, x, stream=stream, keep_device=True)
+    out = torch.empty_like(mid)
+    s2.forward(mid, 3, out, stream)
+    stream.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy(), ref)
+    assert H.rel_err(ref, oracle.stage_forward(H.oracle_cfg(sh), layers, x)) <= H.TOL_BF16
+
+
+def test_determinism_and_workspace_poison():
+    import torch
+    sh = synth.custom_shape("bf_det", 2, 320, 4, 640, 257)
+    layers = layers_of(sh, 2, bf16=True, w_std=0.05)
+    x = synth.activations(sh, 2, bf16=True)
+    st = H.make_stage(sh, layers, 0, 2, 4, bf16=True)
+    a = H.run_stage(st, x)
+    big = H.run_stage(st, synth.activations(sh, 4, bf16=True, tag="other") * 50.0)   # dirty the workspace
+    assert np.isfinite(big).all()
+    b = H.run_stage(st, x)
+    np.testing.assert_array_equal(a, b)
+
+
+# ----------------------------------------------------- the named configurations
+def test_vit_base_stage_of_three_layers_batch_8():
+    sh = synth.SHAPES["vit_base"]
+    layers = layers_of(sh, 3, bf16=True, affine=False)
+    x = synth.activations(sh, 8, bf16=True)
+    st = H.make_stage(sh, layers, 0, 3, 8, bf16=True)
+    got = H.run_stage(st, x)
+    ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x)
+    e = H.rel_err(got, ref)
+    print(f"ViT-Base 3 layers B=8: err {e:.3e}, std {H.err_std(got, ref):.3e}, rms {math.sqrt((ref**2).mean()):.3f}")
+    assert e <= H.TOL_BF16
+
+
+def test_vit_large_stage_of_six_layers_batch_sweep():
+    sh = synth.SHAPES["vit_large"]
+    layers = layers_of(sh, 6, bf16=True, affine=False)
+    st = H.make_stage(sh, layers, 0, 6, 64, bf16=True)
+    # images are independent (section 2.1): image i gives the same result in any batch
+    ref = {i: oracle.stage_forward(H.oracle_cfg(sh), layers, synth.activations(sh, 1, bf16=True, first_image=i))[0]
+           for i in (0, 31)}
+    for B in (1, 4, 16, 32, 64):
+        x = synth.activations(sh, B, bf16=True)
+        got = H.run_stage(st, x)
+        assert np.isfinite(got).all()
+        for i, r in ref.items():
+            if i < B:
+                e = H.rel_err(got[i], r)
+                print(f"ViT-Large 6 layers B={B} image {i}: err {e:.3e}")
+                assert e <= H.TOL_BF16
+        if B > 1:   # the rest of the batch: same statistics as the checked images
+            rms = np.sqrt((got.astype(np.float64) ** 2).mean(axis=(1, 2)))
+            assert np.all(np.abs(rms / rms[0] - 1) < 0.2)
+
+
+def test_vit_huge_all_layers_batch_64_sampled_images():
+    # the benchmark configuration: 32 layers, B=64, T=257; the checker recomputes two images
+    sh = synth.SHAPES["vit_huge"]
+    layers = layers_of(sh, 32, bf16=True, affine=False)
+    st = H.make_stage(sh, layers, 0, 32, 64, bf16=True)
+    x = synth.activations(sh, 64, bf16=True)
+    got = H.run_stage(st, x)
+    assert np.isfinite(got).all()
+    for i in (0, 63):
+        ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x[i:i + 1])[0]
+        e, s = H.rel_err(got[i], ref), H.err_std(got[i], ref)
+        print(f"ViT-Huge 32 layers B=64 image {i}: err {e:.3e}, std {s:.3e}, rms {math.sqrt((ref**2).mean()):.3f}")
+        assert e <= H.TOL_BF16
+    rms = np.sqrt((got.astype(np.float64) ** 2).mean(axis=(1, 2)))
+    assert np.all(np.abs(rms / rms[0] - 1) < 0.2)
