@@ -42,7 +42,7 @@ def build(jobs: int = 8) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         objs = list(pool.map(_compile, sources()))
-    cmd = [HIPCC, "-shared", "-fPIC"] + HIP_FLAGS + ["-o", LIB] + objs
+    cmd = [HIPCC, "-shared", "-fPIC", "-Wl,-z,defs"] + HIP_FLAGS + ["-o", LIB] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")

@@ -35,7 +35,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BK = 64;          // K step (bf16 elements) = 8 chunks of 16 bytes
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 4;
 
@@ -47,21 +46,47 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
     return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(
+#if defined(__HIP_DEVICE_COMPILE__)   // buffer-resource builtins exist only in the device pass
+// Buffer resource over a dense array: loads beyond `bytes` return zero, which is
+// how rows past M (or N) and K tiles past the end are handled without branches.
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+#endif
+
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding)
+#define EP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+
+// Row-dependent XOR applied to the 16-byte chunk index inside an LDS row, for
+// rows of 8 chunks (BK = 64) or 4 chunks (BK = 32).  Chosen so that the MFMA
+// fragment reads (32 consecutive rows, same logical chunk) spread over all
+// banks whether the LDS serves 8 or 16 lanes of a 128-bit read per cycle.
+template <int BK_>
+__device__ inline int swz(int row)
+{
+    if (BK_ == 64) return (row & 7) ^ ((row >> 3) & 1);
+    return ((row >> 1) & 3) ^ ((row >> 3) & 1);
+}
+
+template <int BM, int BN, int BK_, int STAGES, int WM, int WN, int EPI>
+__global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * BK_ * 2 <= 80 * 1024) ? 2 : 1) void gemm_bf16_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const float *__restrict__ bias,
     const float *resid, void *Cout, int M, int N, int K, int tiles_m, int tiles_n)
 {
-    constexpr int NT = WM * WN * 64;
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int NW = WM * WN;                       // waves
     constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
     constexpr int MI = WTM / 32, NI = WTN / 32;       // 32x32 accumulators per wave
-    constexpr int A_LD = BM * 8 / NT, W_LD = BN * 8 / NT;   // 16-byte chunks per thread per step
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "panel must split evenly over threads");
-    static_assert(NT % 8 == 0, "");
+    constexpr int CPR = BK_ / 8;                      // 16-byte chunks per LDS row
+    constexpr int RPI = 64 / CPR;                     // rows covered by one wave-wide 16-byte load
+    constexpr int A_LD = BM / RPI / NW, W_LD = BN / RPI / NW;   // load instructions per wave per tile
+    static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "panel must split evenly over waves");
+    constexpr int A_STAGE = BM * CPR, W_STAGE = BN * CPR;       // uint4 per stage
 
-    extern __shared__ uint4 lds[];                    // [2][BM*8] A panel, then [2][BN*8] W panel
+    extern __shared__ uint4 lds[];                    // [STAGES][A_STAGE] then [STAGES][W_STAGE]
     uint4 *As = lds;
-    uint4 *Ws = lds + 2 * BM * 8;
+    uint4 *Ws = lds + STAGES * A_STAGE;
 
     // ---- workgroup -> tile
     const int total = tiles_m * tiles_n;
@@ -81,25 +106,40 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(
     const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
     const int l31 = lane & 31, g = lane >> 5;
 
-    // ---- global -> register staging
-    const uint16_t *a_src[A_LD];
-    const uint16_t *w_src[W_LD];
-    int a_dst[A_LD], w_dst[W_LD];
+    // ---- global -> LDS, asynchronous (buffer_load ... lds): instruction i of this wave
+    // fills rows (i*NW + wave)*RPI .. +RPI-1 of the panel; lane l lands at row l/CPR,
+    // slot l%CPR, and therefore fetches logical chunk slot ^ swz(row).
+    const __amdgpu_buffer_rsrc_t a_rs = make_rsrc(A, (uint32_t)((size_t)M * K * 2));
+    const __amdgpu_buffer_rsrc_t w_rs = make_rsrc(W, (uint32_t)((size_t)N * K * 2));
+    int a_off[A_LD], w_off[W_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
-        const int id = tid + i * NT, r = id >> 3, c = id & 7;
-        const int gr = min(m0 + r, M - 1);
-        a_src[i] = A + (size_t)gr * K + c * 8;
-        a_dst[i] = r * 8 + (c ^ (r & 7));
+        const int r = (i * NW + wave) * RPI + lane / CPR;
+        const int c = (lane % CPR) ^ swz<BK_>(r);
+        const int gr = m0 + r;
+        a_off[i] = gr < M ? (gr * K + c * 8) * 2 : 0x7FFFFFF0;     // beyond the buffer -> zeros
     }
 #pragma unroll
     for (int i = 0; i < W_LD; ++i) {
-        const int id = tid + i * NT, r = id >> 3, c = id & 7;
-        const int gr = min(n0 + r, N - 1);
-        w_src[i] = W + (size_t)gr * K + c * 8;
-        w_dst[i] = r * 8 + (c ^ (r & 7));
+        const int r = (i * NW + wave) * RPI + lane / CPR;
+        const int c = (lane % CPR) ^ swz<BK_>(r);
+        const int gr = n0 + r;
+        w_off[i] = gr < N ? (gr * K + c * 8) * 2 : 0x7FFFFFF0;
     }
-    uint4 a_reg[A_LD], w_reg[W_LD];
+    const int KT = K / BK_;
+    auto issue = [&](int kt) {
+        const int stage = kt % STAGES;
+        const int koff = kt < KT ? kt * BK_ * 2 : 0x7FFFFFF0;      // past the last tile -> zeros, no traffic
+        typedef __attribute__((address_space(3))) void *lds_ptr;
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                a_rs, (lds_ptr)(As + stage * A_STAGE + (i * NW + wave) * 64), 16, a_off[i], koff, 0, 0);
+#pragma unroll
+        for (int i = 0; i < W_LD; ++i)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                w_rs, (lds_ptr)(Ws + stage * W_STAGE + (i * NW + wave) * 64), 16, w_off[i], koff, 0, 0);
+    };
 
     f32x16 acc[NI][MI];
 #pragma unroll
@@ -109,55 +149,40 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[ni][mi][i] = 0.f;
 
-    const int KT = K / BK;
+    // fragment read offsets (uint4 units) inside a stage; the swizzle depends on the lane only
+    const int fsw = swz<BK_>(l31);
+    int a_rd[BK_ / 16], w_rd[BK_ / 16];
 #pragma unroll
-    for (int i = 0; i < A_LD; ++i) a_reg[i] = *reinterpret_cast<const uint4 *>(a_src[i]);
+    for (int kk = 0; kk < BK_ / 16; ++kk) {
+        a_rd[kk] = (wm0 + l31) * CPR + ((kk * 2 + g) ^ fsw);
+        w_rd[kk] = (wn0 + l31) * CPR + ((kk * 2 + g) ^ fsw);
+    }
+
 #pragma unroll
-    for (int i = 0; i < W_LD; ++i) w_reg[i] = *reinterpret_cast<const uint4 *>(w_src[i]);
-#pragma unroll
-    for (int i = 0; i < A_LD; ++i) As[a_dst[i]] = a_reg[i];
-#pragma unroll
-    for (int i = 0; i < W_LD; ++i) Ws[w_dst[i]] = w_reg[i];
-    __syncthreads();
+    for (int st = 0; st < STAGES - 1; ++st) issue(st);
 
     for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        const bool more = kt + 1 < KT;
-        if (more) {
-            const int koff = (kt + 1) * BK;
+        // tile kt has landed once at most the loads of the STAGES-2 younger tiles are in flight
+        EP_WAIT_VMCNT((STAGES - 2) * (A_LD + W_LD));
+        __builtin_amdgcn_s_barrier();          // everyone's part of tile kt has landed; stage of tile kt-1 is free
+        issue(kt + STAGES - 1);
+        const uint4 *Ab = As + (kt % STAGES) * A_STAGE;
+        const uint4 *Wb = Ws + (kt % STAGES) * W_STAGE;
 #pragma unroll
-            for (int i = 0; i < A_LD; ++i) a_reg[i] = *reinterpret_cast<const uint4 *>(a_src[i] + koff);
-#pragma unroll
-            for (int i = 0; i < W_LD; ++i) w_reg[i] = *reinterpret_cast<const uint4 *>(w_src[i] + koff);
-        }
-        const uint4 *Ab = As + buf * BM * 8;
-        const uint4 *Wb = Ws + buf * BN * 8;
-#pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const int slot = (kk * 2 + g) ^ (lane & 7);
+        for (int kk = 0; kk < BK_ / 16; ++kk) {
             bf16x8 wf[NI], af[MI];
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni)
-                wf[ni] = __builtin_bit_cast(bf16x8, Wb[(wn0 + ni * 32 + l31) * 8 + slot]);
+            for (int ni = 0; ni < NI; ++ni) wf[ni] = __builtin_bit_cast(bf16x8, Wb[w_rd[kk] + ni * 32 * CPR]);
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                af[mi] = __builtin_bit_cast(bf16x8, Ab[(wm0 + mi * 32 + l31) * 8 + slot]);
+            for (int mi = 0; mi < MI; ++mi) af[mi] = __builtin_bit_cast(bf16x8, Ab[a_rd[kk] + mi * 32 * CPR]);
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
                     acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], af[mi], acc[ni][mi], 0, 0, 0);
         }
-        if (more) {
-            uint4 *Ad = As + (buf ^ 1) * BM * 8;
-            uint4 *Wd = Ws + (buf ^ 1) * BN * 8;
-#pragma unroll
-            for (int i = 0; i < A_LD; ++i) Ad[a_dst[i]] = a_reg[i];
-#pragma unroll
-            for (int i = 0; i < W_LD; ++i) Wd[w_dst[i]] = w_reg[i];
-        }
-        __syncthreads();
     }
+    EP_WAIT_VMCNT(0);                          // drain the (empty) tail loads before LDS goes away
 
     // ---- epilogue.  acc[ni][mi][i]: n = ni*32 + 8*(i/4) + 4*g + (i%4), m = mi*32 + (lane&31)
 #pragma unroll
@@ -192,14 +217,15 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_bf16_kernel(
             }
         }
     }
+#endif   // __HIP_DEVICE_COMPILE__
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int BK_, int STAGES, int WM, int WN, int EPI>
 hipError_t launch_cfg(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
                       void *C, int M, int N, int K, hipStream_t s)
 {
-    auto kern = gemm_bf16_kernel<BM, BN, WM, WN, EPI>;
-    constexpr size_t smem = (size_t)2 * (BM + BN) * 8 * sizeof(uint4);
+    auto kern = gemm_bf16_kernel<BM, BN, BK_, STAGES, WM, WN, EPI>;
+    constexpr size_t smem = (size_t)STAGES * (BM + BN) * (BK_ / 8) * sizeof(uint4);
     static bool attr_set = false;   // benign race: the attribute call is idempotent
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -215,34 +241,47 @@ hipError_t launch_cfg(const uint16_t *A, const uint16_t *W, const float *bias, c
     return hipGetLastError();
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int BK_, int STAGES, int WM, int WN>
 hipError_t launch_epi(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
                       void *C, int M, int N, int K, int epi, hipStream_t s)
 {
     switch (epi) {
-    case EPI_BIAS: return launch_cfg<BM, BN, WM, WN, EPI_BIAS>(A, W, bias, resid, C, M, N, K, s);
-    case EPI_BIAS_GELU: return launch_cfg<BM, BN, WM, WN, EPI_BIAS_GELU>(A, W, bias, resid, C, M, N, K, s);
-    case EPI_BIAS_RESID: return launch_cfg<BM, BN, WM, WN, EPI_BIAS_RESID>(A, W, bias, resid, C, M, N, K, s);
+    case EPI_BIAS: return launch_cfg<BM, BN, BK_, STAGES, WM, WN, EPI_BIAS>(A, W, bias, resid, C, M, N, K, s);
+    case EPI_BIAS_GELU: return launch_cfg<BM, BN, BK_, STAGES, WM, WN, EPI_BIAS_GELU>(A, W, bias, resid, C, M, N, K, s);
+    case EPI_BIAS_RESID: return launch_cfg<BM, BN, BK_, STAGES, WM, WN, EPI_BIAS_RESID>(A, W, bias, resid, C, M, N, K, s);
     }
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-int ep_bf16_gemm_num_configs() { return 4; }
+int ep_bf16_gemm_num_configs() { return 14; }
 
 hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, const float *bias,
                                const float *resid, void *C, int64_t M, int N, int K, int epi,
                                hipStream_t s)
 {
     if (M <= 0 || N <= 0) return hipSuccess;
-    if (K <= 0 || K % BK != 0 || N % 4 != 0 || M > (1ll << 30)) return hipErrorInvalidValue;
+    if (K <= 0 || K % 64 != 0 || N % 4 != 0) return hipErrorInvalidValue;
+    // byte offsets inside the kernels are 32-bit
+    if (M * (int64_t)K * 2 >= 0x7FFFFFF0ll || (int64_t)N * K * 2 >= 0x7FFFFFF0ll || M * (int64_t)N >= (1ll << 31))
+        return hipErrorInvalidValue;
     if (epi == EPI_BIAS_RESID && !resid) return hipErrorInvalidValue;
     switch (cfg) {
-    case 0: return launch_epi<256, 256, 2, 4>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 1: return launch_epi<256, 256, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 2: return launch_epi<256, 128, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 3: return launch_epi<128, 128, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 0: return launch_epi<256, 256, 64, 2, 2, 4>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 1: return launch_epi<256, 256, 64, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 2: return launch_epi<256, 128, 64, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 3: return launch_epi<128, 128, 64, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 4: return launch_epi<256, 256, 32, 4, 2, 4>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 5: return launch_epi<256, 256, 32, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 6: return launch_epi<256, 128, 64, 3, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 7: return launch_epi<256, 128, 32, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 8: return launch_epi<128, 128, 64, 3, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 9: return launch_epi<256, 128, 32, 3, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 10: return launch_epi<128, 256, 32, 3, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 11: return launch_epi<128, 128, 32, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 12: return launch_epi<256, 128, 32, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    case 13: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, N, K, epi, s);
     }
     return hipErrorInvalidValue;
 }
@@ -250,8 +289,11 @@ hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, co
 hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
                         void *C, int64_t M, int N, int K, int epi, hipStream_t s)
 {
-    // Small problems: more, smaller tiles so that all 256 CUs get work.
+    // Enough 256x256 tiles for several rounds over all compute units: the persistent
+    // kernel.  Otherwise 128x128 tiles, two workgroups per compute unit, which
+    // quantise better on the narrow (N = D) layers and on small micro-batches.
     const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-    const int cfg = big_tiles >= 512 ? 0 : (big_tiles >= 128 ? 2 : 3);
-    return ep_bf16_gemm_config(cfg, A, W, bias, resid, C, M, N, K, epi, s);
+    if (big_tiles >= 512 && ep_bf16_gemm_persistent_supported(M, N, K))
+        return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, N, K, epi, s);
+    return ep_bf16_gemm_config(3, A, W, bias, resid, C, M, N, K, epi, s);
 }

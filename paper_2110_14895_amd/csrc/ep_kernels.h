@@ -43,3 +43,9 @@ int ep_bf16_gemm_num_configs();
 hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, const float *bias,
                                const float *resid, void *C, int64_t M, int N, int K, int epi,
                                hipStream_t s);
+
+// persistent 256x256 kernel for large problems (ep_gemm_bf16_persist.hip)
+bool ep_bf16_gemm_persistent_supported(int64_t M, int N, int K);
+hipError_t ep_bf16_gemm_persistent(const uint16_t *A, const uint16_t *W, const float *bias,
+                                   const float *resid, void *C, int64_t M, int N, int K, int epi,
+                                   hipStream_t s);
