@@ -203,3 +203,68 @@ def test_vit_huge_all_layers_batch_64_sampled_images():
         assert e <= H.TOL_BF16
     rms = np.sqrt((got.astype(np.float64) ** 2).mean(axis=(1, 2)))
     assert np.all(np.abs(rms / rms[0] - 1) < 0.2)
+
+
+# ------------------------------------------------- profiling, tracing, planning
+def test_profile_and_trace_report_positive_times():
+    import torch
+    sh = synth.custom_shape("bf_prof", 3, 256, 4, 512, 197)
+    layers = layers_of(sh, 3, bf16=True)
+    st = H.make_stage(sh, layers, 0, 3, 8, bf16=True)
+    t = st.profile(8, iters=3)
+    assert t.shape == (3,) and np.all(t > 0) and np.all(t < 1.0)
+    x = synth.activations(sh, 8, bf16=True)
+    ref = H.run_stage(st, x)
+    total = 0.0
+    for kid in range(len(binding.KERNEL_NAMES)):
+        st.trace_begin(kid, 3)
+        got = H.run_stage(st, x)
+        n, sec = st.trace_end()
+        assert n == 3 and sec > 0
+        np.testing.assert_array_equal(got, ref)      # tracing does not change results
+        total += sec
+    assert total < 1.0
+    with pytest.raises(binding.EdgePipeError):
+        st.trace_end()                                # no active trace
+
+
+def test_heterogeneous_partition_stages_match_checker():
+    """Per-layer costs profiled on this GPU feed ep_partition for 16 synthetic devices
+    (seed 1); every resulting uneven stage is run at several micro-batch sizes and
+    compared with the checker on image 0 (images are independent, so one reference per
+    stage serves every batch size) and on the last image of the largest batch."""
+    from oracle import partition as P
+    sh = synth.SHAPES["vit_huge"]
+    B_plan = 8
+    layers = layers_of(sh, 32, bf16=True, affine=False)
+    whole = H.make_stage(sh, layers, 0, 32, B_plan, bf16=True)
+    cost = whole.profile(B_plan, iters=2)
+    whole.destroy()
+    assert cost.shape == (32,) and np.all(cost > 0)
+    inst = synth.heterogeneous_cluster(cost, sh, batch=B_plan, n_devices=16, seed=1)
+    t_opt, plan = binding.partition(inst.t_comp, inst.layer_mem, inst.dev_mem, inst.xfer_bytes, inst.bw)
+    t_ref, _ = P.paper_dp(inst.t_comp, inst.layer_mem, inst.dev_mem, inst.xfer_bytes, inst.bw)
+    assert t_opt == t_ref                                   # bit-exact optimum
+    assert P.evaluate(plan, inst.t_comp, inst.layer_mem, inst.dev_mem, inst.xfer_bytes, inst.bw) == t_opt
+    sizes = [l - f + 1 for _, f, l in plan]
+    print(f"plan: T_opt={t_opt:.4f}s, stages (device, first, last): {plan}")
+    assert sum(sizes) == 32 and len(set(sizes)) > 1         # uneven stages
+    batches = (1, 4, 32, 256)
+    for s_idx, (_dev, first, last) in enumerate(plan):
+        stage_layers = layers[first:last + 1]
+        st = H.make_stage(sh, stage_layers, first, last + 1, max(batches), bf16=True)
+        tag = f"stage{s_idx}"                              # independent N(0,1) input per stage
+        ref0 = oracle.stage_forward(H.oracle_cfg(sh), stage_layers,
+                                    synth.activations(sh, 1, bf16=True, tag=tag))[0]
+        for B in batches:
+            x = synth.activations(sh, B, bf16=True, tag=tag)
+            got = H.run_stage(st, x)
+            assert np.isfinite(got).all()
+            e = H.rel_err(got[0], ref0)
+            assert e <= H.TOL_BF16, (s_idx, B, e)
+            if B == max(batches):
+                ref_last = oracle.stage_forward(H.oracle_cfg(sh), stage_layers, x[B - 1:B])[0]
+                e2 = H.rel_err(got[B - 1], ref_last)
+                print(f"stage {s_idx} layers {first}-{last}: B={B} image 0 err {e:.2e}, image {B-1} err {e2:.2e}")
+                assert e2 <= H.TOL_BF16
+        st.destroy()
