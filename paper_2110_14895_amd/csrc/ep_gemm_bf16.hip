@@ -255,7 +255,7 @@ hipError_t launch_epi(const uint16_t *A, const uint16_t *W, const float *bias, c
 
 }  // namespace
 
-int ep_bf16_gemm_num_configs() { return 14; }
+int ep_bf16_gemm_num_configs() { return 16; }
 
 hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, const float *bias,
                                const float *resid, void *C, int64_t M, int N, int K, int epi,
@@ -281,7 +281,9 @@ hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, co
     case 10: return launch_epi<128, 256, 32, 3, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     case 11: return launch_epi<128, 128, 32, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     case 12: return launch_epi<256, 128, 32, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 13: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, N, K, epi, s);
+    case 13: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 256, s);
+    case 14: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 320, s);
+    case 15: return ep_bf16_gemm_skinny(A, W, bias, resid, C, M, N, K, epi, s);
     }
     return hipErrorInvalidValue;
 }
@@ -289,11 +291,27 @@ hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, co
 hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
                         void *C, int64_t M, int N, int K, int epi, hipStream_t s)
 {
-    // Enough 256x256 tiles for several rounds over all compute units: the persistent
-    // kernel.  Otherwise 128x128 tiles, two workgroups per compute unit, which
-    // quantise better on the narrow (N = D) layers and on small micro-batches.
-    const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-    if (big_tiles >= 512 && ep_bf16_gemm_persistent_supported(M, N, K))
-        return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, N, K, epi, s);
+    // At least one full round of 256-row tiles over the compute units: the persistent kernel.
+    // If M leaves a short remainder after the last full tile and cutting it off saves a round,
+    // the remainder rows go to the short-M kernel.  Otherwise 128x128 tiles, two workgroups
+    // per compute unit, which quantise better on small micro-batches.
+    if (ep_bf16_gemm_persistent_supported(M, N, K)) {
+        int bn_all = 0, bn_main = 0;
+        const int64_t m_main = M / 256 * 256, tail = M - m_main;
+        const int64_t cost_all = ep_bf16_gemm_persistent_cost(M, N, &bn_all);
+        const int64_t tiles_all = ((M + 255) / 256) * ((N + bn_all - 1) / bn_all);
+        if (tail > 0 && tail <= 128 && m_main > 0 && ep_bf16_gemm_skinny_supported(tail, N, K)) {
+            const int64_t cost_main = ep_bf16_gemm_persistent_cost(m_main, N, &bn_main);
+            const int64_t tiles_main = (m_main / 256) * ((N + bn_main - 1) / bn_main);
+            if (cost_main < cost_all && tiles_main >= 192) {
+                hipError_t e = ep_bf16_gemm_persistent(A, W, bias, resid, C, M, m_main, N, K, epi, bn_main, s);
+                if (e != hipSuccess) return e;
+                const size_t csz = epi == EPI_BIAS_RESID ? 4 : 2;
+                return ep_bf16_gemm_skinny(A + m_main * K, W, bias, resid ? resid + m_main * N : nullptr,
+                                           (char *)C + (size_t)m_main * N * csz, tail, N, K, epi, s);
+            }
+        }
+        if (tiles_all >= 192) return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, bn_all, s);
+    }
     return ep_bf16_gemm_config(3, A, W, bias, resid, C, M, N, K, epi, s);
 }

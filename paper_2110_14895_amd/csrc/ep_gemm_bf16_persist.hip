@@ -4,28 +4,30 @@
 //   C[M, N] = A[M, K] . W[N, K]^T + bias[N]   (+ erf GELU | + fp32 residual)
 //
 // One workgroup per compute unit stays resident and walks a static list of
-// 256 x 256 output tiles; the K loop of consecutive tiles forms one continuous
-// software pipeline, so the first K steps of the next tile are already in
-// flight while the current tile is finished and stored.
+// 256 x BN output tiles (BN = 256 or 320, chosen per problem so that the tile
+// count is a multiple of the number of compute units where possible); the K
+// loop of consecutive tiles forms one continuous software pipeline, so the
+// first K step of the next tile is already in LDS when a tile is stored.
 //
-// Pipeline (per workgroup, 8 waves laid out 2 x 4, wave tile 128 x 64):
-//   - K advances in steps of 32.  A step's A and W panels (256 rows x 64 bytes
-//     each) are brought from global memory straight into LDS with
-//     buffer_load ... lds (no register staging), 4 stages deep: the loads of step
-//     i+3 are issued while step i is multiplied.  Each wave issues 4 such loads
-//     per step, interleaved one by one between MFMAs so that their issue cost is
-//     hidden behind matrix-core time.
-//   - LDS rows are 4 chunks of 16 bytes; chunk c of row r sits at slot
-//     c ^ f(r), f(r) = ((r>>1)&3) ^ ((r>>3)&1), which makes the 16-byte fragment
-//     reads of 32 consecutive rows conflict-free on the 64-bank LDS.
-//   - Fragments are double-buffered in registers: the reads for the next
-//     16-wide K slice are issued before the 8 MFMAs of the current slice.
-//   - One barrier per K step, placed before the second slice's MFMAs: it
-//     publishes step i+1 (its loads have landed: vmcnt) and retires step i's
-//     stage for reuse.
-// Epilogue: accumulators (+bias, GELU) are transposed through the LDS stage
-// that has just been retired, one 32-row block per wave at a time, so that
-// global stores (and residual loads) are full 128-byte row segments.
+// Pipeline (per workgroup, 8 waves, two per SIMD):
+//   - K advances in steps of 64 (rows of 128 bytes = whole cache lines, which the
+//     L2 -> LDS path moves ~1.6x faster than half lines).  A step's A and W
+//     panels go from global memory straight into LDS with buffer_load ... lds
+//     (no register staging), two stages; the loads a wave issues per step are
+//     slipped one by one between the MFMAs of the step's last 16-wide slice,
+//     right after the barrier that retires the stage they overwrite, so they have
+//     a whole step to land.
+//   - LDS rows are 8 chunks of 16 bytes; chunk c of row r sits at slot
+//     c ^ f(r), f(r) = (r & 7) ^ ((r >> 3) & 1): the 16-byte fragment reads of 32
+//     consecutive rows are conflict-free on the 64-bank LDS.
+//   - Fragments are double-buffered in registers and every LDS read of the
+//     next slice is issued between two MFMAs of the current one, so a wave has
+//     no phase without matrix work except the one barrier per step.
+// Epilogue: 32 x 32 accumulator blocks (+bias, GELU) are transposed through the
+// LDS stage the tile's last step has just retired (4 KB per wave), so that
+// global stores and residual loads are whole row segments; the refill of that
+// stage for the next tile is issued right after.  Bias comes through the scalar
+// cache.
 //
 // Operand roles are swapped (MFMA A = W fragment, B = activation fragment) so
 // that a lane owns 4 consecutive output columns of one row.
@@ -34,8 +36,10 @@
 // workgroups of an XCD take 32 consecutive tiles of an order that walks groups
 // of 4 tile rows column by column, so that they share A and W panels in L2.
 //
-// Requirements: K % 32 == 0, N % 8 == 0; M*K*2, N*K*2 < 2^31; rows past M and
-// columns past N are read as zeros (buffer bounds) and never stored.
+// Requirements: K % 64 == 0, K >= 128, N % 8 == 0; M*K*2, N*K*2 < 2^31.  Rows
+// past M and columns past N are read as zeros (per-lane buffer offsets beyond
+// the end of the buffer) and never stored.  `m_rows` <= M limits the rows this
+// launch computes (the remaining rows are left to the caller).
 #include "ep_kernels.h"
 
 namespace {
@@ -43,17 +47,44 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 256, BN = 256, BK = 32, STAGES = 4;
-constexpr int WM = 2, WN = 4, NW = WM * WN;          // 8 waves
-constexpr int MI = 4, NI = 2;                        // 32x32 accumulators per wave: 128 (m) x 64 (n)
-constexpr int CPR = BK / 8;                          // 4 chunks of 16 B per LDS row
-constexpr int A_STAGE = BM * CPR, W_STAGE = BN * CPR;   // uint4 per stage and operand
-constexpr int STAGE_U4 = A_STAGE + W_STAGE;          // 2048 uint4 = 32 KB
+constexpr int BM = 256, BK = 64, STAGES = 2;
+constexpr int NW = 8;                                // waves
+constexpr int CPR = BK / 8;                          // 8 chunks of 16 B per LDS row
+constexpr int NSL = BK / 16;                         // 16-wide K slices per step
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 4;
-constexpr size_t SMEM_BYTES = (size_t)STAGES * STAGE_U4 * sizeof(uint4);   // 128 KB
 
-__device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
+// Tile shape: BN columns, waves laid out WM x WN, wave tile (BM/WM) x (BN/WN).
+template <int BN_, int WM_, int WN_>
+struct Tile {
+    static constexpr int BN = BN_, WM = WM_, WN = WN_;
+    static constexpr int MI = BM / WM / 32, NI = BN / WN / 32;        // 32x32 accumulators per wave
+    static constexpr int A_STAGE = BM * CPR, W_STAGE = BN * CPR;      // uint4 per stage and operand
+    static constexpr int STAGE_U4 = A_STAGE + W_STAGE;
+    static constexpr int LDA = BM / 8 / NW, LDW = BN / 8 / NW;        // loads per wave per step (8 rows each)
+    static constexpr size_t SMEM = (size_t)STAGES * STAGE_U4 * sizeof(uint4);
+    static_assert(WM * WN == NW && BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BN % (8 * NW) == 0, "tile shape");
+    static_assert(LDA + LDW <= MI * NI, "one load per MFMA of the last slice");
+    static_assert(MI + NI <= MI * NI, "one fragment read per MFMA");
+    static_assert(STAGE_U4 >= NW * 256, "a stage must hold 4 KB of epilogue staging per wave");
+};
+typedef Tile<256, 2, 4> Tile256;                     // wave tile 128 x 64
+typedef Tile<320, 4, 2> Tile320;                     // wave tile 64 x 160
+
+// erf by Abramowitz & Stegun 7.1.26 (absolute error < 1.5e-7, far below bf16 resolution):
+// gelu(u) = u/2 * (1 + erf(u / sqrt 2))
+__device__ inline float gelu_fast(float u)
+{
+    const float x = fabsf(u) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
+    float p = fmaf(1.061405429f, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    const float e = p * t * __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);   // 1 - erf(x)
+    const float erf_abs = 1.0f - e;
+    return 0.5f * u * (1.0f + copysignf(erf_abs, u));
+}
 
 __device__ inline uint32_t pack_bf16x2(float lo, float hi)
 {
@@ -61,22 +92,27 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
     return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
 }
 
-#define EP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+#define EP_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0 | (0x0 << 14) | (0x7 << 4) | (0xF << 8))
 #define EP_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8))
 #define EP_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-__device__ inline int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
+__device__ inline int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
-template <int EPI>
+template <class T, int EPI>
 __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const float *__restrict__ bias,
-    const float *resid, void *Cout, int M, int N, int K, int tiles_m, int tiles_n)
+    const float *resid, void *Cout, int M, int m_rows, int N, int K, int tiles_m, int tiles_n)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int BN = T::BN, WN = T::WN, MI = T::MI, NI = T::NI;
+    constexpr int A_STAGE = T::A_STAGE, STAGE_U4 = T::STAGE_U4, LDA = T::LDA, LDW = T::LDW;
+    constexpr int NMFMA = MI * NI;
+
     extern __shared__ uint4 lds[];                   // [STAGES][A panel | W panel]
     typedef __attribute__((address_space(3))) void *lds_ptr;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: wave-derived addressing stays scalar
     const int wm0 = (wave / WN) * (MI * 32), wn0 = (wave % WN) * (NI * 32);
     const int l31 = lane & 31, g = lane >> 5;
 
@@ -100,40 +136,48 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
         n0 = (in_group / rows) * BN;
     };
 
-    // ---- load stream (runs STAGES-1 steps ahead of the multiply stream)
+    // ---- load stream: one K step ahead of the multiply stream
     const __amdgpu_buffer_rsrc_t a_rs =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(A), 0, (int)((size_t)M * K * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t w_rs =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(W), 0, (int)((size_t)N * K * 2), 0x00020000);
     constexpr int OOB = 0x7FFFFFF0;
+    // load i of a wave fills panel rows (i*NW + wave)*8 .. +7; lane l lands at row l/8, slot l%8 and
+    // fetches chunk slot ^ swz(row); swz sees the row only through l/8 and the parity of wave (NW
+    // is even), so one per-lane offset serves every i.  Out-of-range handling relies on the per-lane
+    // (VGPR) offset alone, which the buffer bounds check always covers.
+    const int row_lane = wave * 8 + (lane >> 3);
+    const int lane_off = (row_lane * K + ((lane & 7) ^ swz(row_lane)) * 8) * 2;
+    const int istride = NW * 8 * K * 2;              // bytes between loads i and i+1
     int ld_seq = 0, ld_kt = 0, ld_stage = 0;
-    int a_off[2], w_off[2];
+    int a_tile = OOB, w_tile = OOB;                  // byte offset of the tile's first A / W row, or OOB
+    int a_rows = 0, w_rows = 0;                      // valid panel rows of the tile
     auto set_load_tile = [&](int seq) {
         int m0 = 0, n0 = 0;
         const bool live = seq < n_my;
         if (live) tile_origin(seq, m0, n0);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int r = (i * NW + wave) * 16 + (lane >> 2);       // row inside the 256-row panel
-            const int c = (lane & 3) ^ swz(r);
-            const int gm = m0 + r, gn = n0 + r;
-            a_off[i] = (live && gm < M) ? (gm * K + c * 8) * 2 : OOB;
-            w_off[i] = (live && gn < N) ? (gn * K + c * 8) * 2 : OOB;
-        }
+        a_tile = live ? m0 * K * 2 : OOB;
+        w_tile = live ? n0 * K * 2 : OOB;
+        a_rows = live ? M - m0 : 0;
+        w_rows = live ? N - n0 : 0;
     };
-    // which: 0,1 = A panel rows (which*128 + wave*16 ..), 2,3 = W panel likewise
+    // which: 0 .. LDA-1 = A panel, LDA .. LDA+LDW-1 = W panel
     auto issue_one = [&](int which) {
         const int koff = ld_kt * (BK * 2);
         uint4 *dst = lds + ld_stage * STAGE_U4;
-        if (which < 2)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rs, (lds_ptr)(dst + (which * NW + wave) * 64), 16,
-                                                     a_off[which], koff, 0, 0);
-        else
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr)(dst + A_STAGE + ((which - 2) * NW + wave) * 64),
-                                                     16, w_off[which - 2], koff, 0, 0);
+        if (which < LDA) {
+            const bool ok = which * NW * 8 + row_lane < a_rows;
+            const int vo = ok ? lane_off + a_tile + which * istride : OOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rs, (lds_ptr)(dst + (which * NW + wave) * 64), 16, vo, koff, 0, 0);
+        } else {
+            const int i = which - LDA;
+            const bool ok = i * NW * 8 + row_lane < w_rows;
+            const int vo = ok ? lane_off + w_tile + i * istride : OOB;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr)(dst + A_STAGE + (i * NW + wave) * 64), 16, vo, koff, 0, 0);
+        }
     };
     auto advance_load = [&]() {
-        ld_stage = (ld_stage + 1) & (STAGES - 1);
+        ld_stage ^= 1;
         if (++ld_kt == KT) {
             ld_kt = 0;
             set_load_tile(++ld_seq);
@@ -142,19 +186,13 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 
     // ---- fragment reads: offsets in uint4 inside a stage
     const int fsw = swz(l31);
-    int a_rd[2], w_rd[2];
-#pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-        a_rd[kk] = (wm0 + l31) * CPR + ((kk * 2 + g) ^ fsw);
-        w_rd[kk] = A_STAGE + (wn0 + l31) * CPR + ((kk * 2 + g) ^ fsw);
-    }
+    const int a_row = (wm0 + l31) * CPR, w_row = A_STAGE + (wn0 + l31) * CPR;
     bf16x8 fa[2][MI], fw[2][NI];
-    auto read_frags = [&](int stage, int kk, int buf) {
-        const uint4 *base = lds + stage * STAGE_U4;
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni) fw[buf][ni] = __builtin_bit_cast(bf16x8, base[w_rd[kk] + ni * 32 * CPR]);
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) fa[buf][mi] = __builtin_bit_cast(bf16x8, base[a_rd[kk] + mi * 32 * CPR]);
+    // j = 0 .. NI-1: W fragment j; j = NI .. NI+MI-1: A fragment j-NI (the order the MFMAs first need them)
+    auto read_frag = [&](const uint4 *base, int slice, int buf, int j) {
+        const int col = (slice * 2 + g) ^ fsw;
+        if (j < NI) fw[buf][j] = __builtin_bit_cast(bf16x8, base[w_row + j * 32 * CPR + col]);
+        else fa[buf][j - NI] = __builtin_bit_cast(bf16x8, base[a_row + (j - NI) * 32 * CPR + col]);
     };
 
     f32x16 acc[NI][MI];
@@ -166,182 +204,223 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[ni][mi][i] = 0.f;
     };
-    // 8 MFMAs of one 16-wide K slice, with two global->LDS loads slipped in between
-    auto mfma_slice = [&](int buf, int ld_a, int ld_b) {
-        acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][0], fa[buf][0], acc[0][0], 0, 0, 0);
-        acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][1], fa[buf][0], acc[1][0], 0, 0, 0);
-        EP_SCHED_FENCE();
-        issue_one(ld_a);
-        EP_SCHED_FENCE();
-        acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][0], fa[buf][1], acc[0][1], 0, 0, 0);
-        acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][1], fa[buf][1], acc[1][1], 0, 0, 0);
-        acc[0][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][0], fa[buf][2], acc[0][2], 0, 0, 0);
-        acc[1][2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][1], fa[buf][2], acc[1][2], 0, 0, 0);
-        EP_SCHED_FENCE();
-        issue_one(ld_b);
-        EP_SCHED_FENCE();
-        acc[0][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][0], fa[buf][3], acc[0][3], 0, 0, 0);
-        acc[1][3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][1], fa[buf][3], acc[1][3], 0, 0, 0);
+    // MFMA q of a slice: ni fastest
+    auto mfma_one = [&](int buf, int q) {
+        const int ni = q % NI, mi = q / NI;
+        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][ni], fa[buf][mi], acc[ni][mi], 0, 0, 0);
     };
 
-    // ---- epilogue of the tile at (m0, n0); `stage` is free LDS (32 KB, 4 KB per wave)
+    // bias[nb .. nb+7] through the scalar cache (nb is wave-uniform), so that the epilogue does not
+    // wait on the vector-memory counter; the lane keeps the half that belongs to its 4 columns
+    auto bias4 = [&](int nb) {
+        const int u = __builtin_amdgcn_readfirstlane(nb);
+        float lo0 = 0.f, lo1 = 0.f, lo2 = 0.f, lo3 = 0.f, hi0 = 0.f, hi1 = 0.f, hi2 = 0.f, hi3 = 0.f;
+        if (u < N) {                                 // N % 8 == 0: all eight or none
+            lo0 = bias[u + 0]; lo1 = bias[u + 1]; lo2 = bias[u + 2]; lo3 = bias[u + 3];
+            hi0 = bias[u + 4]; hi1 = bias[u + 5]; hi2 = bias[u + 6]; hi3 = bias[u + 7];
+        }
+        return g ? make_float4(hi0, hi1, hi2, hi3) : make_float4(lo0, lo1, lo2, lo3);
+    };
+
+    // ---- epilogue of the tile at (m0, n0); `stage` has just been retired and is free LDS.
+    // acc[ni][mi][i] <-> column ni*32 + 8*(i/4) + 4*g + (i%4), row mi*32 + (lane&31).
     auto epilogue = [&](int m0, int n0, int stage) {
-        uint4 *stg = lds + stage * STAGE_U4 + wave * 256;          // 256 uint4 = 4 KB, rows of 128 B
-        const int rrow = lane >> 3, rc = lane & 7;                  // read-back: 8 rows x 8 chunks per pass
-        if (EPI == EPI_BIAS_RESID) {
-            float *C = reinterpret_cast<float *>(Cout);
+        uint4 *stg = lds + stage * STAGE_U4 + wave * 256;           // 4 KB
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
+        for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
-                    // block [32 m][32 n] fp32: chunk = 4 floats, 8 chunks per row
+            for (int ni = 0; ni < NI; ++ni) {
+                const int nblk = n0 + wn0 + ni * 32, mblk = m0 + wm0 + mi * 32;
+                if (EPI == EPI_BIAS_RESID) {
+                    // block [32 m][32 n] fp32: rows of 128 B = 8 chunks of 4 floats
+                    float *C = reinterpret_cast<float *>(Cout);
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const int n = n0 + wn0 + ni * 32 + q * 8 + g * 4;
-                        float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (n < N) bb = *reinterpret_cast<const float4 *>(bias + n);
-                        float4 v = make_float4(acc[ni][mi][q * 4 + 0] + bb.x, acc[ni][mi][q * 4 + 1] + bb.y,
-                                               acc[ni][mi][q * 4 + 2] + bb.z, acc[ni][mi][q * 4 + 3] + bb.w);
+                        const float4 bb = bias4(nblk + q * 8);
+                        const float4 v = make_float4(acc[ni][mi][q * 4 + 0] + bb.x, acc[ni][mi][q * 4 + 1] + bb.y,
+                                                     acc[ni][mi][q * 4 + 2] + bb.z, acc[ni][mi][q * 4 + 3] + bb.w);
                         *reinterpret_cast<float4 *>(&stg[l31 * 8 + ((q * 2 + g) ^ (l31 & 7))]) = v;
+                    }
+                    const int rrow = lane >> 3, rc = lane & 7;      // read-back: 8 rows x 8 chunks per pass
+                    float4 v[4], x[4];
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        const int r = p * 8 + rrow, m = mblk + r, n = nblk + rc * 4;
+                        x[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (m < m_rows && n < N) x[p] = *reinterpret_cast<const float4 *>(resid + (size_t)m * N + n);
+                        v[p] = *reinterpret_cast<const float4 *>(&stg[r * 8 + (rc ^ (r & 7))]);
                     }
 #pragma unroll
                     for (int p = 0; p < 4; ++p) {
-                        const int r = p * 8 + rrow;
-                        const float4 v = *reinterpret_cast<const float4 *>(&stg[r * 8 + (rc ^ (r & 7))]);
-                        const int m = m0 + wm0 + mi * 32 + r;
-                        const int n = n0 + wn0 + ni * 32 + rc * 4;
-                        if (m < M && n < N) {
-                            const size_t off = (size_t)m * N + n;
-                            const float4 x = *reinterpret_cast<const float4 *>(resid + off);
-                            *reinterpret_cast<float4 *>(C + off) = make_float4(v.x + x.x, v.y + x.y, v.z + x.z, v.w + x.w);
-                        }
+                        const int r = p * 8 + rrow, m = mblk + r, n = nblk + rc * 4;
+                        if (m < m_rows && n < N)
+                            *reinterpret_cast<float4 *>(C + (size_t)m * N + n) =
+                                make_float4(v[p].x + x[p].x, v[p].y + x[p].y, v[p].z + x[p].z, v[p].w + x[p].w);
                     }
-                }
-            }
-        } else {
-            uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) {
-                // block [32 m][64 n] bf16: chunk = 8 bf16, 8 chunks per row
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni) {
+                } else {
+                    // block [32 m][32 n] bf16: rows of 64 B = 4 chunks of 8 bf16
+                    uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const int n = n0 + wn0 + ni * 32 + q * 8 + g * 4;
-                        float4 bb = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (n < N) bb = *reinterpret_cast<const float4 *>(bias + n);
+                        const float4 bb = bias4(nblk + q * 8);
                         float v0 = acc[ni][mi][q * 4 + 0] + bb.x, v1 = acc[ni][mi][q * 4 + 1] + bb.y;
                         float v2 = acc[ni][mi][q * 4 + 2] + bb.z, v3 = acc[ni][mi][q * 4 + 3] + bb.w;
                         if (EPI == EPI_BIAS_GELU) {
-                            v0 = gelu_erf(v0); v1 = gelu_erf(v1); v2 = gelu_erf(v2); v3 = gelu_erf(v3);
+                            v0 = gelu_fast(v0); v1 = gelu_fast(v1); v2 = gelu_fast(v2); v3 = gelu_fast(v3);
                         }
                         uint2 o;
                         o.x = pack_bf16x2(v0, v1);
                         o.y = pack_bf16x2(v2, v3);
-                        uint2 *dst = reinterpret_cast<uint2 *>(&stg[l31 * 8 + ((ni * 4 + q) ^ (l31 & 7))]) + g;
-                        *dst = o;
+                        reinterpret_cast<uint2 *>(&stg[l31 * 4 + (q ^ (l31 & 3))])[g] = o;
                     }
-                }
+                    const int rrow = lane >> 2, rc = lane & 3;      // read-back: 16 rows x 4 chunks per pass
 #pragma unroll
-                for (int p = 0; p < 4; ++p) {
-                    const int r = p * 8 + rrow;
-                    const uint4 v = stg[r * 8 + (rc ^ (r & 7))];
-                    const int m = m0 + wm0 + mi * 32 + r;
-                    const int n = n0 + wn0 + rc * 8;
-                    if (m < M && n < N) *reinterpret_cast<uint4 *>(C + (size_t)m * N + n) = v;
+                    for (int p = 0; p < 2; ++p) {
+                        const int r = p * 16 + rrow, m = mblk + r, n = nblk + rc * 8;
+                        const uint4 v = stg[r * 4 + (rc ^ (r & 3))];
+                        if (m < m_rows && n < N) *reinterpret_cast<uint4 *>(C + (size_t)m * N + n) = v;
+                    }
                 }
             }
         }
     };
 
-    // ---- prologue: fill STAGES-1 steps
+    // ---- prologue: step 0 into stage 0, wait, first fragments; then step 1 into stage 1
     set_load_tile(0);
 #pragma unroll
-    for (int st = 0; st < STAGES - 1; ++st) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) issue_one(q);
-        advance_load();
-    }
+    for (int q = 0; q < LDA + LDW; ++q) issue_one(q);
+    advance_load();
     zero_acc();
-    EP_WAIT_VMCNT(8);                               // step 0 landed (steps 1, 2 may be in flight)
+    EP_WAIT_VMCNT0();
     __builtin_amdgcn_s_barrier();
-    read_frags(0, 0, 0);
+#pragma unroll
+    for (int j = 0; j < NI + MI; ++j) read_frag(lds, 0, 0, j);
+#pragma unroll
+    for (int q = 0; q < LDA + LDW; ++q) issue_one(q);
+    advance_load();
 
     int c_seq = 0, c_kt = 0;
-    bool after_store = false;
     for (int it = 0; it < total_it; ++it) {
-        const int s = it & (STAGES - 1);
-        // slice 0: prefetch slice 1 of this step, multiply slice 0, issue the A loads of step it+3
-        read_frags(s, 1, 1);
-        EP_SCHED_FENCE();
-        mfma_slice(0, 0, 1);
-        EP_SCHED_FENCE();
-        // slice 1: publish step it+1, retire this step's stage
-        EP_WAIT_LGKMCNT0();                         // my reads of stage s are done
-        if (after_store) EP_WAIT_VMCNT(0); else EP_WAIT_VMCNT(6);   // step it+1 landed
-        after_store = false;
+        const uint4 *cur = lds + (it & 1) * STAGE_U4;
+        const uint4 *nxt = lds + ((it + 1) & 1) * STAGE_U4;
+        const bool tile_end = c_kt == KT - 1;
+        // slices 0 .. NSL-2: multiply slice sl (buffer sl&1) while reading slice sl+1
+#pragma unroll
+        for (int sl = 0; sl < NSL - 1; ++sl) {
+#pragma unroll
+            for (int q = 0; q < NMFMA; ++q) {
+                mfma_one(sl & 1, q);
+                if (q < NI + MI) read_frag(cur, sl + 1, (sl + 1) & 1, q);
+                EP_SCHED_FENCE();
+            }
+        }
+        // all my reads of this stage are done; the next step has landed; swap
+        EP_WAIT_LGKMCNT0();
+        EP_WAIT_VMCNT0();
         __builtin_amdgcn_s_barrier();
-        read_frags((it + 1) & (STAGES - 1), 0, 0);
-        EP_SCHED_FENCE();
-        mfma_slice(1, 2, 3);
-        EP_SCHED_FENCE();
-        advance_load();
-        if (++c_kt == KT) {
+        // last slice: read the next step's first fragments and refill the retired stage
+        // (at the end of a tile the stage first serves the epilogue and is refilled after it)
+#pragma unroll
+        for (int q = 0; q < NMFMA; ++q) {
+            mfma_one((NSL - 1) & 1, q);
+            if (q < NI + MI) read_frag(nxt, 0, 0, q);
+            if (q < LDA + LDW && !tile_end) issue_one(q);
+            EP_SCHED_FENCE();
+        }
+        if (tile_end) {
             int m0, n0;
             tile_origin(c_seq, m0, n0);
-            epilogue(m0, n0, s);                    // stage s was retired by the barrier above
+            epilogue(m0, n0, it & 1);
             zero_acc();
             c_kt = 0;
             ++c_seq;
-            after_store = true;
-            __builtin_amdgcn_s_barrier();           // staging reads done before stage s is refilled
+            EP_WAIT_LGKMCNT0();
+            __builtin_amdgcn_s_barrier();           // every wave is done with the staging area
+#pragma unroll
+            for (int q = 0; q < LDA + LDW; ++q) issue_one(q);
+        } else {
+            ++c_kt;
         }
+        advance_load();
     }
-    EP_WAIT_VMCNT(0);                               // drain the dummy tail loads before LDS is released
+    EP_WAIT_VMCNT0();                               // drain the tail loads before LDS is released
 #endif
 }
 
-template <int EPI>
+int g_grid = 0;
+
+template <class T, int EPI>
 hipError_t launch_persistent(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
-                             void *C, int M, int N, int K, hipStream_t s)
+                             void *C, int M, int m_rows, int N, int K, hipStream_t s)
 {
-    auto kern = gemm_bf16_persistent_kernel<EPI>;
+    auto kern = gemm_bf16_persistent_kernel<T, EPI>;
     static bool attr_set = false;
-    static int grid_cached = 0;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM_BYTES);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::SMEM);
         if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    if (!g_grid) {
+        hipError_t e;
         int dev = 0, cus = 0;
         if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
         if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-        grid_cached = cus / NUM_XCD * NUM_XCD;
-        if (grid_cached < NUM_XCD) grid_cached = NUM_XCD;
-        attr_set = true;
+        g_grid = cus / NUM_XCD * NUM_XCD;
+        if (g_grid < NUM_XCD) g_grid = NUM_XCD;
     }
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    hipLaunchKernelGGL(kern, dim3(grid_cached), dim3(NW * 64), SMEM_BYTES, s, A, W, bias, resid, C, M, N, K,
+    const int tiles_m = (m_rows + BM - 1) / BM, tiles_n = (N + T::BN - 1) / T::BN;
+    hipLaunchKernelGGL(kern, dim3(g_grid), dim3(NW * 64), T::SMEM, s, A, W, bias, resid, C, M, m_rows, N, K,
                        tiles_m, tiles_n);
     return hipGetLastError();
+}
+
+template <class T>
+hipError_t launch_tile(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid, void *C,
+                       int M, int m_rows, int N, int K, int epi, hipStream_t s)
+{
+    switch (epi) {
+    case EPI_BIAS: return launch_persistent<T, EPI_BIAS>(A, W, bias, resid, C, M, m_rows, N, K, s);
+    case EPI_BIAS_GELU: return launch_persistent<T, EPI_BIAS_GELU>(A, W, bias, resid, C, M, m_rows, N, K, s);
+    case EPI_BIAS_RESID: return launch_persistent<T, EPI_BIAS_RESID>(A, W, bias, resid, C, M, m_rows, N, K, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+// Rounds of tiles over `cus` compute units, weighted by the tile width: the cost of a tile
+// shape for this problem.
+int64_t tile_cost(int64_t rows, int N, int bn, int cus)
+{
+    const int64_t tiles = ((rows + BM - 1) / BM) * ((N + bn - 1) / bn);
+    return (tiles + cus - 1) / cus * bn;
 }
 
 }  // namespace
 
 bool ep_bf16_gemm_persistent_supported(int64_t M, int N, int K)
 {
-    return M > 0 && N > 0 && K >= BK * STAGES && K % BK == 0 && N % 8 == 0 &&
+    return M > 0 && N > 0 && K >= 2 * BK && K % BK == 0 && N % 8 == 0 &&
            M * (int64_t)K * 2 < 0x7FFFFFF0ll && (int64_t)N * K * 2 < 0x7FFFFFF0ll && M * (int64_t)N < (1ll << 31);
 }
 
-hipError_t ep_bf16_gemm_persistent(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
-                                   void *C, int64_t M, int N, int K, int epi, hipStream_t s)
+int64_t ep_bf16_gemm_persistent_cost(int64_t rows, int N, int *tile_bn)
 {
-    if (!ep_bf16_gemm_persistent_supported(M, N, K)) return hipErrorInvalidValue;
+    const int cus = g_grid ? g_grid : 256;
+    const int64_t c256 = tile_cost(rows, N, 256, cus), c320 = tile_cost(rows, N, 320, cus);
+    if (tile_bn) *tile_bn = c320 < c256 ? 320 : 256;
+    return c320 < c256 ? c320 : c256;
+}
+
+// tile_bn: 0 = choose, else 256 or 320.  m_rows <= M: only rows [0, m_rows) are computed.
+hipError_t ep_bf16_gemm_persistent(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
+                                   void *C, int64_t M, int64_t m_rows, int N, int K, int epi, int tile_bn,
+                                   hipStream_t s)
+{
+    if (!ep_bf16_gemm_persistent_supported(M, N, K) || m_rows < 0 || m_rows > M) return hipErrorInvalidValue;
     if (epi == EPI_BIAS_RESID && !resid) return hipErrorInvalidValue;
-    switch (epi) {
-    case EPI_BIAS: return launch_persistent<EPI_BIAS>(A, W, bias, resid, C, (int)M, N, K, s);
-    case EPI_BIAS_GELU: return launch_persistent<EPI_BIAS_GELU>(A, W, bias, resid, C, (int)M, N, K, s);
-    case EPI_BIAS_RESID: return launch_persistent<EPI_BIAS_RESID>(A, W, bias, resid, C, (int)M, N, K, s);
-    }
+    if (m_rows == 0) return hipSuccess;
+    if (tile_bn == 0) (void)ep_bf16_gemm_persistent_cost(m_rows, N, &tile_bn);
+    if (tile_bn == 320) return launch_tile<Tile320>(A, W, bias, resid, C, (int)M, (int)m_rows, N, K, epi, s);
+    if (tile_bn == 256) return launch_tile<Tile256>(A, W, bias, resid, C, (int)M, (int)m_rows, N, K, epi, s);
     return hipErrorInvalidValue;
 }
