@@ -35,6 +35,7 @@
 // Template: DH = head width (multiple of 16), NKT = number of 32-key tiles the
 // LDS buffers hold (T <= 32*NKT, NKT a multiple of 3).
 #include "ep_kernels.h"
+#include "ep_device.h"
 #include <algorithm>
 
 namespace {
@@ -42,14 +43,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-__device__ inline uint32_t pack_bf16x2(float lo, float hi)   // one v_cvt_pk_bf16_f32 (round to nearest even)
-{
-    const f32x2 v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
 
 constexpr int CH = 3;                              // 32-key tiles per chunk
 

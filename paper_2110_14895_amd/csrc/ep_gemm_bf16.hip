@@ -7,12 +7,16 @@
 // A: bf16 activations, W: bf16 weights [out, in], both K-contiguous, fp32
 // accumulation on the matrix cores (v_mfma_f32_32x32x16_bf16).
 //
-// Tiling.  A workgroup owns a BM x BN tile of C and walks K in steps of 64.
-// Each K step's A and W panels live in LDS as rows of eight 16-byte chunks;
-// chunk c of row r is stored at slot c ^ (r & 7), which makes both the 16-byte
-// panel writes and the MFMA fragment reads bank-conflict free without padding.
-// Global loads for step k+1 are issued into registers before the MFMAs of step
-// k and written to the other LDS buffer afterwards (one barrier per step).
+// This file holds the one-tile-per-workgroup kernel used for problems too small
+// for the persistent kernel (ep_gemm_bf16_persist.hip), the table of tile
+// configurations behind ep_bf16_gemm_config, and the dispatcher ep_bf16_gemm.
+//
+// Tiling.  A workgroup owns a BM x BN tile of C and walks K in steps of BK (64
+// or 32).  Each K step's A and W panels live in LDS as rows of 16-byte chunks;
+// chunk c of row r is stored at slot c ^ f(r) (f below), which makes the MFMA
+// fragment reads bank-conflict free without padding.  The panels go from global
+// memory straight into LDS (buffer_load ... lds), STAGES - 1 steps ahead of the
+// MFMAs, with explicit s_waitcnt counts and one bare s_barrier per step.
 // Waves are laid out WM x WN; each wave keeps (BN/WN/32) x (BM/WM/32)
 // accumulators of 32x32.
 //
@@ -26,9 +30,16 @@
 // inside an XCD tiles are visited in groups of GROUP_M tile rows so that
 // concurrently running workgroups share A row panels and W column panels.
 //
-// Ragged edges: rows beyond M and columns beyond N are loaded from the last
-// valid row (clamped) and never stored.  K % 64 == 0 and N % 4 == 0 required.
+// Ragged edges: rows beyond M and columns beyond N are read as zeros (per-lane
+// buffer offsets past the end of the buffer) and never stored.  K % 64 == 0 and
+// N % 8 == 0 required.
+//
+// Dispatcher: rows up to the last multiple of 256 go to the persistent kernel
+// when that fills the chip; a remainder of at most 128 rows goes to the short-M
+// split-K kernel (ep_gemm_bf16_skinny.hip) when that lowers the number of tile
+// rounds; everything else runs here.
 #include "ep_kernels.h"
+#include "ep_device.h"
 
 namespace {
 
@@ -38,13 +49,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 4;
 
-__device__ inline float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
-
-__device__ inline uint32_t pack_bf16x2(float lo, float hi)
-{
-    const __bf16 a = (__bf16)lo, b = (__bf16)hi;   // round to nearest even
-    return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
-}
 
 #if defined(__HIP_DEVICE_COMPILE__)   // buffer-resource builtins exist only in the device pass
 // Buffer resource over a dense array: loads beyond `bytes` return zero, which is
@@ -129,16 +133,19 @@ __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * 
     const int KT = K / BK_;
     auto issue = [&](int kt) {
         const int stage = kt % STAGES;
-        const int koff = kt < KT ? kt * BK_ * 2 : 0x7FFFFFF0;      // past the last tile -> zeros, no traffic
+        // past the last K step the per-lane offset points beyond the buffer: zeros, no traffic (the
+        // load is still issued so that the count of loads in flight stays fixed)
+        const bool live = kt < KT;
+        const int koff = live ? kt * BK_ * 2 : 0;
         typedef __attribute__((address_space(3))) void *lds_ptr;
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                a_rs, (lds_ptr)(As + stage * A_STAGE + (i * NW + wave) * 64), 16, a_off[i], koff, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rs, (lds_ptr)(As + stage * A_STAGE + (i * NW + wave) * 64), 16,
+                                                     live ? a_off[i] : 0x7FFFFFF0, koff, 0, 0);
 #pragma unroll
         for (int i = 0; i < W_LD; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                w_rs, (lds_ptr)(Ws + stage * W_STAGE + (i * NW + wave) * 64), 16, w_off[i], koff, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rs, (lds_ptr)(Ws + stage * W_STAGE + (i * NW + wave) * 64), 16,
+                                                     live ? w_off[i] : 0x7FFFFFF0, koff, 0, 0);
     };
 
     f32x16 acc[NI][MI];
@@ -255,7 +262,7 @@ hipError_t launch_epi(const uint16_t *A, const uint16_t *W, const float *bias, c
 
 }  // namespace
 
-int ep_bf16_gemm_num_configs() { return 16; }
+int ep_bf16_gemm_num_configs() { return 17; }
 
 hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, const float *bias,
                                const float *resid, void *C, int64_t M, int N, int K, int epi,
@@ -283,13 +290,33 @@ hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, co
     case 12: return launch_epi<256, 128, 32, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     case 13: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 256, s);
     case 14: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 320, s);
-    case 15: return ep_bf16_gemm_skinny(A, W, bias, resid, C, M, N, K, epi, s);
+    case 15: return ep_bf16_gemm_skinny(A, W, bias, resid, C, M, N, K, epi, nullptr, 0, s);
+    case 16: {
+        // K-split variant; the sweep hook has no workspace argument, so it keeps one of its own
+        static float *ws = nullptr;
+        static size_t ws_floats = 0;
+        const size_t need = ep_bf16_gemm_skinny_workspace_floats(M, N);
+        if (need > ws_floats) {
+            if (ws) (void)hipFree(ws);
+            ws = nullptr; ws_floats = 0;
+            hipError_t e = hipMalloc((void **)&ws, need * sizeof(float));
+            if (e != hipSuccess) return e;
+            ws_floats = need;
+        }
+        return ep_bf16_gemm_skinny(A, W, bias, resid, C, M, N, K, epi, ws, ws_floats, s);
+    }
     }
     return hipErrorInvalidValue;
 }
 
+size_t ep_bf16_gemm_workspace_floats(int64_t M, int N)
+{
+    const int64_t tail = M % 256;                    // the only rows the short-M kernel ever gets
+    return tail > 0 && tail <= 128 ? ep_bf16_gemm_skinny_workspace_floats(tail, N) : 0;
+}
+
 hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
-                        void *C, int64_t M, int N, int K, int epi, hipStream_t s)
+                        void *C, int64_t M, int N, int K, int epi, float *ws, size_t ws_floats, hipStream_t s)
 {
     // At least one full round of 256-row tiles over the compute units: the persistent kernel.
     // If M leaves a short remainder after the last full tile and cutting it off saves a round,
@@ -308,7 +335,7 @@ hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias,
                 if (e != hipSuccess) return e;
                 const size_t csz = epi == EPI_BIAS_RESID ? 4 : 2;
                 return ep_bf16_gemm_skinny(A + m_main * K, W, bias, resid ? resid + m_main * N : nullptr,
-                                           (char *)C + (size_t)m_main * N * csz, tail, N, K, epi, s);
+                                           (char *)C + (size_t)m_main * N * csz, tail, N, K, epi, ws, ws_floats, s);
             }
         }
         if (tiles_all >= 192) return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, bn_all, s);

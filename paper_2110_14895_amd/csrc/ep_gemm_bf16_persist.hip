@@ -41,6 +41,7 @@
 // the end of the buffer) and never stored.  `m_rows` <= M limits the rows this
 // launch computes (the remaining rows are left to the caller).
 #include "ep_kernels.h"
+#include "ep_device.h"
 
 namespace {
 
@@ -71,26 +72,6 @@ struct Tile {
 typedef Tile<256, 2, 4> Tile256;                     // wave tile 128 x 64
 typedef Tile<320, 4, 2> Tile320;                     // wave tile 64 x 160
 
-// erf by Abramowitz & Stegun 7.1.26 (absolute error < 1.5e-7, far below bf16 resolution):
-// gelu(u) = u/2 * (1 + erf(u / sqrt 2))
-__device__ inline float gelu_fast(float u)
-{
-    const float x = fabsf(u) * 0.70710678118654752440f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
-    float p = fmaf(1.061405429f, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    const float e = p * t * __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);   // 1 - erf(x)
-    const float erf_abs = 1.0f - e;
-    return 0.5f * u * (1.0f + copysignf(erf_abs, u));
-}
-
-__device__ inline uint32_t pack_bf16x2(float lo, float hi)
-{
-    const __bf16 a = (__bf16)lo, b = (__bf16)hi;   // round to nearest even
-    return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
-}
 
 #define EP_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0 | (0x0 << 14) | (0x7 << 4) | (0xF << 8))
 #define EP_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8))
@@ -266,7 +247,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                         float v0 = acc[ni][mi][q * 4 + 0] + bb.x, v1 = acc[ni][mi][q * 4 + 1] + bb.y;
                         float v2 = acc[ni][mi][q * 4 + 2] + bb.z, v3 = acc[ni][mi][q * 4 + 3] + bb.w;
                         if (EPI == EPI_BIAS_GELU) {
-                            v0 = gelu_fast(v0); v1 = gelu_fast(v1); v2 = gelu_fast(v2); v3 = gelu_fast(v3);
+                            v0 = gelu_erf(v0); v1 = gelu_erf(v1); v2 = gelu_erf(v2); v3 = gelu_erf(v3);
                         }
                         uint2 o;
                         o.x = pack_bf16x2(v0, v1);

@@ -3,74 +3,86 @@
 //
 //   C[M, N] = A[M, K] . W[N, K]^T + bias[N]   (+ erf GELU | + fp32 residual),  M small
 //
-// Such a problem has too few output tiles to fill the chip and a long K, so it
-// is latency-bound.  Each workgroup owns a 64 x 32 output tile (narrow, so that
-// many compute units pull the weights in parallel) and splits K eight ways over
-// its 8 waves; a wave streams its K range straight from global memory into MFMA
-// fragments (no LDS staging: every byte is used once), ten 16-wide slices
-// (30 loads) in flight at a time, and accumulates a private 64 x 32 partial.  The eight partials are summed through LDS in a fixed order
-// (wave 0 .. 7, so the result does not depend on timing), then bias / GELU /
-// residual are applied and 4 consecutive columns per thread are stored.
+// Such a problem has few output tiles and a long K, so it is bound by latency
+// and by how many compute units pull the weights at once.  The work is cut
+// three ways: 64 x 32 output tiles (narrow, many of them), for long K (>= 2560)
+// K split over up to 8 workgroups per tile (so that there are about two
+// workgroups per compute unit), and inside a workgroup the 16-wide K slices
+// dealt round-robin to its 8 waves.  A wave streams its slices straight from global memory into MFMA
+// fragments (no LDS staging: every byte is used once), up to six slices
+// (18 loads) in flight, and accumulates a private 64 x 32 partial.  The eight
+// partials of a workgroup are summed through LDS in a fixed order (wave 0 .. 7).
+// Without a K split the workgroup then applies bias / GELU / residual and
+// stores; with one it writes its partial tile to a workspace and a second small
+// kernel sums the splits, again in a fixed order, and applies the epilogue.
+// The result does not depend on timing in either case.
 //
-// Requirements: K % 128 == 0, N % 8 == 0.  Rows past M and columns past N are
-// read as zeros (per-lane buffer offsets past the end) and never stored.
+// Requirements: K % 16 == 0, N % 8 == 0, M <= 4096.  Rows past M and columns
+// past N are read as zeros (per-lane buffer offsets past the end) and never
+// stored.
 #include "ep_kernels.h"
+#include "ep_device.h"
 
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int TM = 64, TN = 32, NW = 8, U = 10;
+constexpr int TM = 64, TN = 32, NW = 8, U = 6, MAX_SPLIT = 8;
 constexpr size_t SMEM = (size_t)NW * TM * TN * sizeof(float);
 
-__device__ inline float gelu_fast(float u)
+template <int EPI>
+__device__ inline void store_epilogue(float v[4], const float *bias, const float *resid, void *Cout, int m, int n,
+                                      int N)
 {
-    // erf by Abramowitz & Stegun 7.1.26, absolute error < 1.5e-7
-    const float x = fabsf(u) * 0.70710678118654752440f;
-    const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, x, 1.0f));
-    float p = fmaf(1.061405429f, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    const float e = p * t * __builtin_amdgcn_exp2f(-x * x * 1.4426950408889634f);
-    return 0.5f * u * (1.0f + copysignf(1.0f - e, u));
+    const float4 b0 = *reinterpret_cast<const float4 *>(bias + n);
+    v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
+    const size_t off = (size_t)m * N + n;
+    if (EPI == EPI_BIAS_RESID) {
+        const float4 x0 = *reinterpret_cast<const float4 *>(resid + off);
+        float *C = reinterpret_cast<float *>(Cout);
+        *reinterpret_cast<float4 *>(C + off) = make_float4(v[0] + x0.x, v[1] + x0.y, v[2] + x0.z, v[3] + x0.w);
+    } else {
+        if (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = gelu_erf(v[j]);
+        }
+        uint2 o;
+        o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(Cout) + off) = o;
+    }
 }
 
-__device__ inline uint32_t pack_bf16x2(float lo, float hi)
-{
-    const __bf16 a = (__bf16)lo, b = (__bf16)hi;
-    return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
-}
-
+// grid: x = column tiles, y = row tiles, z = K splits of kw elements each.  part == nullptr: no split.
 template <int EPI>
 __global__ __launch_bounds__(NW * 64) void gemm_bf16_skinny_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const float *__restrict__ bias,
-    const float *resid, void *Cout, int M, int N, int K)
+    const float *resid, void *Cout, float *__restrict__ part, int M, int N, int K, int kw)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     extern __shared__ float part_raw[];              // [NW][TM][TN] fp32 = 64 KB
-    float (*part)[TM][TN] = reinterpret_cast<float (*)[TM][TN]>(part_raw);
+    float (*wsum)[TM][TN] = reinterpret_cast<float (*)[TM][TN]>(part_raw);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, g = lane >> 5;
     const int m0 = blockIdx.y * TM, n0 = blockIdx.x * TN;
+    const int k0 = blockIdx.z * kw;
 
     const __amdgpu_buffer_rsrc_t a_rs =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(A), 0, (int)((size_t)M * K * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t w_rs =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(W), 0, (int)((size_t)N * K * 2), 0x00020000);
     constexpr int OOB = 0x7FFFFFF0;
-    const int kw = K / NW;                           // this wave's K range: [wave*kw, (wave+1)*kw)
-    const int nsl = kw / 16;
+    const int nsl = kw / 16;                         // slices of this workgroup; wave w takes w, w+8, ...
+    const int my_nsl = (nsl - wave + NW - 1) / NW;
     // fragment f (0,1): rows f*32 + l31 of the tile, 8 elements at k + g*8
     int a_off[2], w_off;
 #pragma unroll
     for (int f = 0; f < 2; ++f) {
         const int am = m0 + f * 32 + l31;
-        a_off[f] = am < M ? (am * K + wave * kw + g * 8) * 2 : OOB;
+        a_off[f] = am < M ? (am * K + k0 + wave * 16 + g * 8) * 2 : OOB;
     }
-    w_off = n0 + l31 < N ? ((n0 + l31) * K + wave * kw + g * 8) * 2 : OOB;
+    w_off = n0 + l31 < N ? ((n0 + l31) * K + k0 + wave * 16 + g * 8) * 2 : OOB;
 
     f32x16 acc[2];
 #pragma unroll
@@ -78,13 +90,13 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_skinny_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[mi][i] = 0.f;
 
-    for (int s0 = 0; s0 < nsl; s0 += U) {
+    for (int s0 = 0; s0 < my_nsl; s0 += U) {
         __builtin_amdgcn_sched_barrier(0);
         bf16x8 fa[U][2], fw[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const bool live = s0 + u < nsl;          // wave-uniform
-            const int ko = (s0 + u) * 32;            // bytes
+            const bool live = s0 + u < my_nsl;       // wave-uniform
+            const int ko = (s0 + u) * NW * 32;       // bytes: my slices are NW * 16 elements apart
             fw[u] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(w_rs, live ? w_off + ko : OOB, 0, 0));
 #pragma unroll
             for (int f = 0; f < 2; ++f)
@@ -103,7 +115,7 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_skinny_kernel(
     for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-            *reinterpret_cast<float4 *>(&part[wave][mi * 32 + l31][q * 8 + g * 4]) =
+            *reinterpret_cast<float4 *>(&wsum[wave][mi * 32 + l31][q * 8 + g * 4]) =
                 make_float4(acc[mi][q * 4 + 0], acc[mi][q * 4 + 1], acc[mi][q * 4 + 2], acc[mi][q * 4 + 3]);
     __syncthreads();
 
@@ -112,33 +124,61 @@ __global__ __launch_bounds__(NW * 64) void gemm_bf16_skinny_kernel(
     float v[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
-        const float4 p0 = *reinterpret_cast<const float4 *>(&part[w][r][c]);
+        const float4 p0 = *reinterpret_cast<const float4 *>(&wsum[w][r][c]);
         v[0] += p0.x; v[1] += p0.y; v[2] += p0.z; v[3] += p0.w;
     }
     const int m = m0 + r, n = n0 + c;
     if (m >= M || n >= N) return;
-    const float4 b0 = *reinterpret_cast<const float4 *>(bias + n);
-    v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
-    const size_t off = (size_t)m * N + n;
-    if (EPI == EPI_BIAS_RESID) {
-        const float4 x0 = *reinterpret_cast<const float4 *>(resid + off);
-        float *C = reinterpret_cast<float *>(Cout);
-        *reinterpret_cast<float4 *>(C + off) = make_float4(v[0] + x0.x, v[1] + x0.y, v[2] + x0.z, v[3] + x0.w);
-    } else {
-        if (EPI == EPI_BIAS_GELU) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = gelu_fast(v[j]);
-        }
-        uint2 o;
-        o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
-        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(Cout) + off) = o;
+    if (part) {
+        *reinterpret_cast<float4 *>(part + ((size_t)blockIdx.z * M + m) * N + n) = make_float4(v[0], v[1], v[2], v[3]);
+        return;
     }
+    store_epilogue<EPI>(v, bias, resid, Cout, m, n, N);
 #endif
+}
+
+// sums the K splits (in order) and applies the epilogue; one thread per 4 columns
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_skinny_reduce_kernel(const float *__restrict__ part, int splits,
+                                                                      const float *__restrict__ bias,
+                                                                      const float *resid, void *Cout, int M, int N)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int n4 = N / 4;
+    if (i >= (int64_t)M * n4) return;
+    const int m = (int)(i / n4), n = (int)(i % n4) * 4;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int z = 0; z < splits; ++z) {
+        const float4 p = *reinterpret_cast<const float4 *>(part + ((size_t)z * M + m) * N + n);
+        v[0] += p.x; v[1] += p.y; v[2] += p.z; v[3] += p.w;
+    }
+    store_epilogue<EPI>(v, bias, resid, Cout, m, n, N);
+}
+
+int pick_splits(int M, int N, int K, size_t ws_floats)
+{
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu <= 0)
+            n_cu = 256;
+    }
+    const int tiles = ((N + TN - 1) / TN) * ((M + TM - 1) / TM);
+    int splits = 1;
+    // a second launch costs about as much as 20 slices per wave take: split long K only
+    if (K < 2560) return 1;
+    // double while that keeps every split a whole number of slices, at least one slice per wave,
+    // inside the workspace, and the grid at or below about two workgroups per compute unit
+    while (splits * 2 <= MAX_SPLIT && K % (splits * 2 * 16) == 0 && K / (splits * 2) >= NW * 16 &&
+           (size_t)(splits * 2) * M * N <= ws_floats && tiles * splits * 2 <= 2 * n_cu + n_cu / 4)
+        splits *= 2;
+    return splits;
 }
 
 template <int EPI>
 hipError_t launch_skinny(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid, void *C,
-                         int M, int N, int K, hipStream_t s)
+                         int M, int N, int K, float *ws, size_t ws_floats, hipStream_t s)
 {
     auto kern = gemm_bf16_skinny_kernel<EPI>;
     static bool attr_set = false;
@@ -148,8 +188,15 @@ hipError_t launch_skinny(const uint16_t *A, const uint16_t *W, const float *bias
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const dim3 grid((N + TN - 1) / TN, (M + TM - 1) / TM);
-    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), SMEM, s, A, W, bias, resid, C, M, N, K);
+    const int splits = ws ? pick_splits(M, N, K, ws_floats) : 1;
+    const dim3 grid((N + TN - 1) / TN, (M + TM - 1) / TM, splits);
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), SMEM, s, A, W, bias, resid, C, splits > 1 ? ws : nullptr, M, N, K,
+                       K / splits);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splits == 1) return e;
+    const int64_t threads = (int64_t)M * (N / 4);
+    hipLaunchKernelGGL(gemm_bf16_skinny_reduce_kernel<EPI>, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+                       ws, splits, bias, resid, C, M, N);
     return hipGetLastError();
 }
 
@@ -157,19 +204,22 @@ hipError_t launch_skinny(const uint16_t *A, const uint16_t *W, const float *bias
 
 bool ep_bf16_gemm_skinny_supported(int64_t M, int N, int K)
 {
-    return M > 0 && M <= 4096 && N > 0 && N % 8 == 0 && K >= 128 && K % 128 == 0 &&
+    return M > 0 && M <= 4096 && N > 0 && N % 8 == 0 && K >= 16 && K % 16 == 0 &&
            M * (int64_t)K * 2 < 0x7FFFFFF0ll && (int64_t)N * K * 2 < 0x7FFFFFF0ll;
 }
 
+size_t ep_bf16_gemm_skinny_workspace_floats(int64_t M, int N) { return (size_t)MAX_SPLIT * (size_t)M * (size_t)N; }
+
 hipError_t ep_bf16_gemm_skinny(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
-                               void *C, int64_t M, int N, int K, int epi, hipStream_t s)
+                               void *C, int64_t M, int N, int K, int epi, float *ws, size_t ws_floats,
+                               hipStream_t s)
 {
     if (!ep_bf16_gemm_skinny_supported(M, N, K)) return hipErrorInvalidValue;
     if (epi == EPI_BIAS_RESID && !resid) return hipErrorInvalidValue;
     switch (epi) {
-    case EPI_BIAS: return launch_skinny<EPI_BIAS>(A, W, bias, resid, C, (int)M, N, K, s);
-    case EPI_BIAS_GELU: return launch_skinny<EPI_BIAS_GELU>(A, W, bias, resid, C, (int)M, N, K, s);
-    case EPI_BIAS_RESID: return launch_skinny<EPI_BIAS_RESID>(A, W, bias, resid, C, (int)M, N, K, s);
+    case EPI_BIAS: return launch_skinny<EPI_BIAS>(A, W, bias, resid, C, (int)M, N, K, ws, ws_floats, s);
+    case EPI_BIAS_GELU: return launch_skinny<EPI_BIAS_GELU>(A, W, bias, resid, C, (int)M, N, K, ws, ws_floats, s);
+    case EPI_BIAS_RESID: return launch_skinny<EPI_BIAS_RESID>(A, W, bias, resid, C, (int)M, N, K, ws, ws_floats, s);
     }
     return hipErrorInvalidValue;
 }

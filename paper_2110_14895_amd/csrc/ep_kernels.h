@@ -26,10 +26,13 @@ hipError_t ep_bf16_layernorm(const float *x, const float *g, const float *b, flo
                              uint16_t *y, int64_t rows, int D, hipStream_t s);
 hipError_t ep_bf16_to_f32(const uint16_t *in, float *out, int64_t n, hipStream_t s);
 hipError_t ep_f32_to_bf16(const float *in, uint16_t *out, int64_t n, hipStream_t s);
-// A bf16 [M, K], W bf16 [N, K]; out bf16 (EPI_BIAS, EPI_BIAS_GELU) or fp32 (EPI_BIAS_RESID)
+// A bf16 [M, K], W bf16 [N, K]; out bf16 (EPI_BIAS, EPI_BIAS_GELU) or fp32 (EPI_BIAS_RESID).
+// ws: device scratch of ws_floats floats for the K-split partial sums of the short-M kernel
+// (ep_bf16_gemm_workspace_floats says how much serves a given problem; may be null: no K split).
 hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias,
                         const float *resid, void *C, int64_t M, int N, int K, int epi,
-                        hipStream_t s);
+                        float *ws, size_t ws_floats, hipStream_t s);
+size_t ep_bf16_gemm_workspace_floats(int64_t M, int N);
 // qkv bf16 [B*T, 3D] -> o bf16 [B*T, D]
 hipError_t ep_bf16_attention(const uint16_t *qkv, uint16_t *o, int B, int T, int D, int H,
                              hipStream_t s);
@@ -54,8 +57,10 @@ hipError_t ep_bf16_gemm_persistent(const uint16_t *A, const uint16_t *W, const f
                                    const float *resid, void *C, int64_t M, int64_t m_rows, int N,
                                    int K, int epi, int tile_bn, hipStream_t s);
 
-// short-M kernel (ep_gemm_bf16_skinny.hip): 64 x 64 tiles, K split over the 8 waves of a workgroup
+// short-M kernel (ep_gemm_bf16_skinny.hip): 64 x 32 tiles, K split over workgroups (partials in
+// ws, summed by a second kernel) and over the 8 waves of a workgroup
 bool ep_bf16_gemm_skinny_supported(int64_t M, int N, int K);
+size_t ep_bf16_gemm_skinny_workspace_floats(int64_t M, int N);
 hipError_t ep_bf16_gemm_skinny(const uint16_t *A, const uint16_t *W, const float *bias,
                                const float *resid, void *C, int64_t M, int N, int K, int epi,
-                               hipStream_t s);
+                               float *ws, size_t ws_floats, hipStream_t s);

@@ -7,6 +7,7 @@
 // registers, one pass over memory), fp32 statistics, round-to-nearest-even
 // narrowing.  Algorithmic traffic per row: 4*D bytes read, 2*D written.
 #include "ep_kernels.h"
+#include "ep_device.h"
 
 namespace {
 
@@ -17,12 +18,6 @@ __device__ inline float wave_sum(float v)
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, WAVE);
     return v;
-}
-
-__device__ inline uint32_t pack_bf16x2(float lo, float hi)
-{
-    const __bf16 a = (__bf16)lo, b = (__bf16)hi;   // fptrunc: round to nearest even
-    return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
 }
 
 // NV = number of float4 per lane (D = 256 * NV exactly, or ragged when GUARD)
