@@ -18,6 +18,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16
+# HBM bytes per launch of the dominant kernel at the headline workload, from two rocprofv3 --pmc
+# runs of this script (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the
+# input conversion kernel, whose traffic is known: 337.1 MB fetched + 171.0 MB written
+# (profiles/vit_huge_b64_fc1_hbm_traffic.md).  Valid for the kernel as profiled; set to None when
+# the kernel changes until the counters are taken again.
+FC1_MAIN_TRAFFIC_BYTES = 337.1e6 + 171.0e6
 
 
 def main() -> int:
@@ -73,27 +79,32 @@ def main() -> int:
     flops_per_step = B * n_layers * sh.flops_per_image_per_layer()
     tflops = flops_per_step / (dt / args.steps) / 1e12
 
-    # ---- dominant kernel: FC1 (+GELU) GEMM, events around each of its launches in a second
-    # pass over the same steps
+    # ---- dominant kernel: the persistent GEMM launch of FC1 (+GELU), HIP events around each of
+    # its launches (recorded inside the library on the stream it launches on) in a second pass
+    # over the same steps; the other kernels of the layer are timed the same way for the split.
     R = B * sh.n_tokens
     roofline = None
     kernels = {}
-    ids = range(len(binding.KERNEL_NAMES)) if not args.no_kernel_split else [5]
+    fc1_main = binding.MAIN_KERNEL_IDS["fc1"]
+    ids = list(range(len(binding.KERNEL_NAMES))) + [fc1_main] if not args.no_kernel_split else [fc1_main]
     for kid in ids:
-        steps = args.steps if kid == 5 else min(args.steps, 3)
+        steps = args.steps if kid == fc1_main else min(args.steps, 3)
         stage.trace_begin(kid, n_layers * steps)
         for _ in range(steps):
             stage.forward(xin, B, out, stream)
         torch.cuda.synchronize()
         n, sec = stage.trace_end()
-        kernels[binding.KERNEL_NAMES[kid]] = sec / n * 1e6 if n else None
-        if kid == 5 and n:
-            fl = 2.0 * R * sh.d_model * sh.d_mlp
+        if kid < len(binding.KERNEL_NAMES):
+            kernels[binding.KERNEL_NAMES[kid]] = sec / n * 1e6 if n else None
+        elif n:
+            rows = stage.gemm_main_rows(B, kid)          # rows this launch covers (whole 256-row tiles)
+            fl = 2.0 * rows * sh.d_model * sh.d_mlp
             achieved = fl / (sec / n) / 1e12
-            roofline = {"kernel": "fc1_gelu_gemm", "bound": "mfma", "achieved": round(achieved, 2),
+            roofline = {"kernel": "fc1_gelu_gemm_main_launch", "bound": "mfma", "achieved": round(achieved, 2),
                         "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                        "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": None,
-                        "avg_us": round(sec / n * 1e6, 2), "launches": n,
+                        "frac": round(achieved / PEAK_BF16_MFMA_TFLOPS, 4),
+                        "traffic": FC1_MAIN_TRAFFIC_BYTES if (B, sh.name, n_layers) == (64, "vit_huge", 32) else None,
+                        "avg_us": round(sec / n * 1e6, 2), "launches": n, "rows": rows,
                         "flop_per_launch": fl}
 
     result = {

@@ -141,7 +141,18 @@ typedef enum {
     EP_K_LN2 = 4,  /* LayerNorm before the MLP */
     EP_K_FC1 = 5,  /* first dense layer + GELU */
     EP_K_FC2 = 6,  /* second dense layer + residual */
-    EP_K_COUNT = 7
+    EP_K_COUNT = 7,
+    /*
+     * A dense layer may take two launches: one over the rows of whole 256-row
+     * tiles and a small one over the row remainder.  These ids time the first
+     * launch alone (bf16 path only; it is the whole layer when there is no second
+     * launch); ep_stage_gemm_main_rows gives the rows it covers.
+     */
+    EP_K_QKV_MAIN = 7,
+    EP_K_PROJ_MAIN = 8,
+    EP_K_FC1_MAIN = 9,
+    EP_K_FC2_MAIN = 10,
+    EP_K_TRACE_COUNT = 11
 } ep_kernel_id;
 
 /*
@@ -157,6 +168,13 @@ ep_status ep_stage_trace_begin(ep_stage_t *stage, int32_t kernel, int32_t max_la
  * launches and the sum of their durations in seconds (HOST), frees the events.
  */
 ep_status ep_stage_trace_end(ep_stage_t *stage, int32_t *launches, double *seconds);
+
+/*
+ * Rows of the B*T activation rows that the first launch of dense layer `kernel`
+ * (EP_K_QKV, EP_K_PROJ, EP_K_FC1, EP_K_FC2 or their _MAIN ids) covers at
+ * micro-batch B: what a roofline figure for that launch has to count.
+ */
+ep_status ep_stage_gemm_main_rows(const ep_stage_t *stage, int32_t B, int32_t kernel, int64_t *rows);
 
 /* Device bytes held by the stage (parameters + workspace). */
 ep_status ep_stage_device_bytes(const ep_stage_t *stage, uint64_t *bytes);

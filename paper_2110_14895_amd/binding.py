@@ -20,6 +20,8 @@ EP_OK, EP_ERR_INVALID_ARG, EP_ERR_UNSUPPORTED, EP_ERR_OOM, EP_ERR_HIP, EP_ERR_IN
 EP_F32, EP_BF16 = 0, 1
 
 KERNEL_NAMES = ("ln1", "qkv", "attn", "proj", "ln2", "fc1", "fc2")   # ep_kernel_id order
+# ids that time the first launch of a dense layer alone (EP_K_*_MAIN)
+MAIN_KERNEL_IDS = {"qkv": 7, "proj": 8, "fc1": 9, "fc2": 10}
 PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
                "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 
@@ -61,6 +63,7 @@ def lib() -> C.CDLL:
         L.ep_stage_profile.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, dp]
         L.ep_stage_trace_begin.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         L.ep_stage_trace_end.argtypes = [C.c_void_p, ip, dp]
+        L.ep_stage_gemm_main_rows.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int64)]
         L.ep_stage_device_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
         L.ep_stage_destroy.argtypes = [C.c_void_p]
         L.ep_stage_destroy.restype = None
@@ -70,7 +73,7 @@ def lib() -> C.CDLL:
         L.ep_last_error.argtypes = []
         L.ep_last_error.restype = C.c_char_p
         for f in (L.ep_stage_create, L.ep_stage_forward, L.ep_stage_profile, L.ep_stage_trace_begin,
-                  L.ep_stage_trace_end, L.ep_stage_device_bytes, L.ep_partition):
+                  L.ep_stage_trace_end, L.ep_stage_gemm_main_rows, L.ep_stage_device_bytes, L.ep_partition):
             f.restype = C.c_int
         _lib = L
     return _lib
@@ -165,6 +168,11 @@ class Stage:
         n, sec = C.c_int32(), C.c_double()
         _check(lib().ep_stage_trace_end(self._h, C.byref(n), C.byref(sec)), "ep_stage_trace_end")
         return int(n.value), float(sec.value)
+
+    def gemm_main_rows(self, batch: int, kernel: int) -> int:
+        v = C.c_int64()
+        _check(lib().ep_stage_gemm_main_rows(self._h, batch, kernel, C.byref(v)), "ep_stage_gemm_main_rows")
+        return int(v.value)
 
     def device_bytes(self) -> int:
         v = C.c_uint64()

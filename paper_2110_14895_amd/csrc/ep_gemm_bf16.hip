@@ -315,8 +315,14 @@ size_t ep_bf16_gemm_workspace_floats(int64_t M, int N)
     return tail > 0 && tail <= 128 ? ep_bf16_gemm_skinny_workspace_floats(tail, N) : 0;
 }
 
-hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
-                        void *C, int64_t M, int N, int K, int epi, float *ws, size_t ws_floats, hipStream_t s)
+namespace {
+
+// How ep_bf16_gemm cuts the problem: rows [0, m_main) go to the persistent kernel with
+// tile width bn (bn = 0: the one-tile-per-workgroup kernel takes all rows), rows
+// [m_main, M) to the short-M kernel.
+struct GemmPlan { int64_t m_main; int bn; };
+
+GemmPlan plan_gemm(int64_t M, int N, int K)
 {
     // At least one full round of 256-row tiles over the compute units: the persistent kernel.
     // If M leaves a short remainder after the last full tile and cutting it off saves a round,
@@ -330,15 +336,28 @@ hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias,
         if (tail > 0 && tail <= 128 && m_main > 0 && ep_bf16_gemm_skinny_supported(tail, N, K)) {
             const int64_t cost_main = ep_bf16_gemm_persistent_cost(m_main, N, &bn_main);
             const int64_t tiles_main = (m_main / 256) * ((N + bn_main - 1) / bn_main);
-            if (cost_main < cost_all && tiles_main >= 192) {
-                hipError_t e = ep_bf16_gemm_persistent(A, W, bias, resid, C, M, m_main, N, K, epi, bn_main, s);
-                if (e != hipSuccess) return e;
-                const size_t csz = epi == EPI_BIAS_RESID ? 4 : 2;
-                return ep_bf16_gemm_skinny(A + m_main * K, W, bias, resid ? resid + m_main * N : nullptr,
-                                           (char *)C + (size_t)m_main * N * csz, tail, N, K, epi, ws, ws_floats, s);
-            }
+            if (cost_main < cost_all && tiles_main >= 192) return {m_main, bn_main};
         }
-        if (tiles_all >= 192) return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, bn_all, s);
+        if (tiles_all >= 192) return {M, bn_all};
     }
-    return ep_bf16_gemm_config(3, A, W, bias, resid, C, M, N, K, epi, s);
+    return {M, 0};
+}
+
+}  // namespace
+
+int64_t ep_bf16_gemm_main_rows(int64_t M, int N, int K) { return plan_gemm(M, N, K).m_main; }
+
+hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
+                        void *C, int64_t M, int N, int K, int epi, float *ws, size_t ws_floats,
+                        hipEvent_t after_main, hipStream_t s)
+{
+    const GemmPlan p = plan_gemm(M, N, K);
+    hipError_t e = p.bn ? ep_bf16_gemm_persistent(A, W, bias, resid, C, M, p.m_main, N, K, epi, p.bn, s)
+                        : ep_bf16_gemm_config(3, A, W, bias, resid, C, M, N, K, epi, s);
+    if (e != hipSuccess) return e;
+    if (after_main && (e = hipEventRecord(after_main, s)) != hipSuccess) return e;
+    if (p.m_main == M) return hipSuccess;
+    const size_t csz = epi == EPI_BIAS_RESID ? 4 : 2;
+    return ep_bf16_gemm_skinny(A + p.m_main * K, W, bias, resid ? resid + p.m_main * N : nullptr,
+                               (char *)C + (size_t)p.m_main * N * csz, M - p.m_main, N, K, epi, ws, ws_floats, s);
 }

@@ -103,24 +103,31 @@ ep_status check_config(const ep_vit_config *c)
     return EP_OK;
 }
 
-// Brackets one kernel launch with an event pair when that kernel is traced.
+// Brackets one kernel of the layer with an event pair when that kernel is traced.  For a dense
+// layer traced under its _MAIN id the closing event is handed to the GEMM dispatcher, which
+// records it right after its first launch.
 struct TraceScope {
-    ep_stage *st; hipStream_t s; bool on;
-    TraceScope(ep_stage *st_, int kernel, hipStream_t s_) : st(st_), s(s_), on(false)
+    ep_stage *st; hipStream_t s; bool on, main_only;
+    TraceScope(ep_stage *st_, int kernel, int main_id, hipStream_t s_) : st(st_), s(s_), on(false), main_only(false)
     {
-        if (st->trace_kernel == kernel && st->trace_used + 2 <= st->trace_ev.size()) {
+        const bool hit = st->trace_kernel == kernel || (main_id >= 0 && st->trace_kernel == main_id);
+        if (hit && st->trace_used + 2 <= st->trace_ev.size()) {
             on = hipEventRecord(st->trace_ev[st->trace_used], s) == hipSuccess;
+            main_only = on && st->trace_kernel == main_id;
         }
     }
+    hipEvent_t after_main() const { return main_only ? st->trace_ev[st->trace_used + 1] : nullptr; }
     ~TraceScope()
     {
         if (on) {
-            (void)hipEventRecord(st->trace_ev[st->trace_used + 1], s);
+            if (!main_only) (void)hipEventRecord(st->trace_ev[st->trace_used + 1], s);
             st->trace_used += 2;
         }
     }
 };
-#define EP_TRACED(kernel, call) do { TraceScope ts_(st, kernel, s); EP_HIP(call); } while (0)
+#define EP_TRACED(kernel, call) do { TraceScope ts_(st, kernel, -1, s); EP_HIP(call); } while (0)
+// `call` may use ts_.after_main()
+#define EP_TRACED_GEMM(kernel, main_id, call) do { TraceScope ts_(st, kernel, main_id, s); EP_HIP(call); } while (0)
 
 // One layer on R = B*T rows.  `xin` is the residual stream read by this layer
 // (may be the caller's fp32 input), the layer leaves its result in `xout`.
@@ -133,12 +140,20 @@ ep_status run_layer(ep_stage *st, const LayerDev &L, const float *xin, float *xo
     if (st->bf16) {
         uint16_t *a = (uint16_t *)st->a, *big = (uint16_t *)st->big;
         EP_TRACED(EP_K_LN1, ep_bf16_layernorm(xin, L.ln1_g, L.ln1_b, c.ln_eps, a, R, D, s));
-        EP_TRACED(EP_K_QKV, ep_bf16_gemm(a, (const uint16_t *)L.w_qkv, L.b_qkv, nullptr, big, R, 3 * D, D, EPI_BIAS, st->part, st->part_floats, s));
+        EP_TRACED_GEMM(EP_K_QKV, EP_K_QKV_MAIN,
+                       ep_bf16_gemm(a, (const uint16_t *)L.w_qkv, L.b_qkv, nullptr, big, R, 3 * D, D, EPI_BIAS, st->part,
+                                    st->part_floats, ts_.after_main(), s));
         EP_TRACED(EP_K_ATTN, ep_bf16_attention(big, a, B, T, D, H, s));
-        EP_TRACED(EP_K_PROJ, ep_bf16_gemm(a, (const uint16_t *)L.w_o, L.b_o, xin, st->x, R, D, D, EPI_BIAS_RESID, st->part, st->part_floats, s));
+        EP_TRACED_GEMM(EP_K_PROJ, EP_K_PROJ_MAIN,
+                       ep_bf16_gemm(a, (const uint16_t *)L.w_o, L.b_o, xin, st->x, R, D, D, EPI_BIAS_RESID, st->part,
+                                    st->part_floats, ts_.after_main(), s));
         EP_TRACED(EP_K_LN2, ep_bf16_layernorm(st->x, L.ln2_g, L.ln2_b, c.ln_eps, a, R, D, s));
-        EP_TRACED(EP_K_FC1, ep_bf16_gemm(a, (const uint16_t *)L.w_fc1, L.b_fc1, nullptr, big, R, M, D, EPI_BIAS_GELU, st->part, st->part_floats, s));
-        EP_TRACED(EP_K_FC2, ep_bf16_gemm(big, (const uint16_t *)L.w_fc2, L.b_fc2, st->x, xout, R, D, M, EPI_BIAS_RESID, st->part, st->part_floats, s));
+        EP_TRACED_GEMM(EP_K_FC1, EP_K_FC1_MAIN,
+                       ep_bf16_gemm(a, (const uint16_t *)L.w_fc1, L.b_fc1, nullptr, big, R, M, D, EPI_BIAS_GELU, st->part,
+                                    st->part_floats, ts_.after_main(), s));
+        EP_TRACED_GEMM(EP_K_FC2, EP_K_FC2_MAIN,
+                       ep_bf16_gemm(big, (const uint16_t *)L.w_fc2, L.b_fc2, st->x, xout, R, D, M, EPI_BIAS_RESID, st->part,
+                                    st->part_floats, ts_.after_main(), s));
     } else {
         float *a = (float *)st->a, *big = (float *)st->big;
         EP_TRACED(EP_K_LN1, ep_f32_layernorm(xin, L.ln1_g, L.ln1_b, c.ln_eps, a, R, D, s));
@@ -338,8 +353,10 @@ extern "C" ep_status ep_stage_profile(ep_stage_t *st, int32_t B, int32_t iters, 
 extern "C" ep_status ep_stage_trace_begin(ep_stage_t *st, int32_t kernel, int32_t max_launches)
 {
     if (!st) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_trace_begin: null stage");
-    if (kernel < 0 || kernel >= EP_K_COUNT || max_launches < 1 || max_launches > (1 << 20))
+    if (kernel < 0 || kernel >= EP_K_TRACE_COUNT || max_launches < 1 || max_launches > (1 << 20))
         return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_trace_begin: bad kernel id or max_launches");
+    if (kernel >= EP_K_COUNT && !st->bf16)
+        return ep_fail(EP_ERR_UNSUPPORTED, "ep_stage_trace_begin: the _MAIN ids exist on the bf16 path only");
     if (st->trace_kernel >= 0) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_trace_begin: a trace is already active");
     st->trace_ev.clear();
     st->trace_ev.reserve((size_t)max_launches * 2);
@@ -377,6 +394,24 @@ extern "C" ep_status ep_stage_trace_end(ep_stage_t *st, int32_t *launches, doubl
     st->trace_used = 0;
     st->trace_kernel = -1;
     return rc;
+}
+
+extern "C" ep_status ep_stage_gemm_main_rows(const ep_stage_t *st, int32_t B, int32_t kernel, int64_t *rows)
+{
+    if (!st || !rows) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_gemm_main_rows: null argument");
+    if (B < 0 || B > st->max_batch) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_gemm_main_rows: batch out of range");
+    const ep_vit_config &c = st->cfg;
+    const int64_t R = (int64_t)B * c.n_tokens;
+    int N = 0, K = 0;
+    switch (kernel) {
+    case EP_K_QKV: case EP_K_QKV_MAIN: N = 3 * c.d_model; K = c.d_model; break;
+    case EP_K_PROJ: case EP_K_PROJ_MAIN: N = c.d_model; K = c.d_model; break;
+    case EP_K_FC1: case EP_K_FC1_MAIN: N = c.d_mlp; K = c.d_model; break;
+    case EP_K_FC2: case EP_K_FC2_MAIN: N = c.d_model; K = c.d_mlp; break;
+    default: return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_gemm_main_rows: kernel %d is not a dense layer", kernel);
+    }
+    *rows = st->bf16 && R > 0 ? ep_bf16_gemm_main_rows(R, N, K) : R;
+    return EP_OK;
 }
 
 extern "C" ep_status ep_stage_device_bytes(const ep_stage_t *st, uint64_t *bytes)

@@ -203,6 +203,10 @@ def test_vit_huge_all_layers_batch_64_sampled_images():
         assert e <= H.TOL_BF16
     rms = np.sqrt((got.astype(np.float64) ** 2).mean(axis=(1, 2)))
     assert np.all(np.abs(rms / rms[0] - 1) < 0.2)
+    # 64 * 257 rows = 64 tiles of 256 rows + 64: every dense layer runs as the persistent launch
+    # over 16384 rows plus the short-M launch (with its K split for the second MLP layer)
+    for kid in binding.MAIN_KERNEL_IDS.values():
+        assert st.gemm_main_rows(64, kid) == 16384
 
 
 # ------------------------------------------------- profiling, tracing, planning
@@ -226,6 +230,21 @@ def test_profile_and_trace_report_positive_times():
     assert total < 1.0
     with pytest.raises(binding.EdgePipeError):
         st.trace_end()                                # no active trace
+    # the ids that time the first launch of a dense layer alone: never longer than the whole
+    # layer, and the rows it covers are all rows when there is no second launch
+    for name, kid in binding.MAIN_KERNEL_IDS.items():
+        st.trace_begin(binding.KERNEL_NAMES.index(name), 3)
+        H.run_stage(st, x)
+        _, whole = st.trace_end()
+        st.trace_begin(kid, 3)
+        got = H.run_stage(st, x)
+        n, sec = st.trace_end()
+        assert n == 3 and 0 < sec <= whole * 1.5 + 1e-4
+        np.testing.assert_array_equal(got, ref)
+        rows = st.gemm_main_rows(8, kid)
+        assert 0 < rows <= 8 * sh.n_tokens and (rows == 8 * sh.n_tokens or rows % 256 == 0)
+    with pytest.raises(binding.EdgePipeError):
+        st.gemm_main_rows(8, 0)                       # LayerNorm is not a dense layer
 
 
 def test_heterogeneous_partition_stages_match_checker():
