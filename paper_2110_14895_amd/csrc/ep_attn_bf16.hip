@@ -4,13 +4,15 @@
 //
 // Persistent workgroups, one per compute unit (the LDS footprint allows no
 // more), each walking a list of (image, head) pairs; one wavefront per tile of
-// 32 query tokens (at most 9, T <= 288).  K (row-major) and V (transposed:
-// [component][token]) of the head are staged in LDS and shared by all query
-// tiles; the first four waves, which finish their tiles first, fetch the next
-// pair's K and V into registers while the others still compute.  A wave walks
-// the keys in chunks of 96 and computes the transposed score tile
-// S^T = K . Q^T with v_mfma_f32_32x32x16_bf16: the accumulator layout then puts
-// one query per lane column and the keys inside the lane, so
+// 32 query tokens (at most 9, T <= 288) plus three producer waves.  K
+// (row-major) and V (transposed: [component][token]) of the head are staged in
+// LDS and shared by all query tiles; the producer waves load the next pair's K
+// and V into registers while the query waves work on the current pair, and
+// write them to LDS (transposing V) once the pair is retired, so the memory
+// latency of a pair hides behind the arithmetic of the one before.  A query
+// wave walks the keys in chunks of 96 and computes the transposed score tile
+// S^T = K . Q^T with v_mfma_f32_32x32x16_bf16: the accumulator layout then
+// puts one query per lane column and the keys inside the lane, so
 //   - the chunk maximum is an in-lane reduction plus one exchange between the
 //     two half-waves; the reference maximum of the exponentials follows the
 //     true maximum lazily (the accumulated output is rescaled only when some
@@ -28,9 +30,9 @@
 //     the sum is accumulated on the vector ALU from the unrounded values.
 // Softmax is fp32: exp2 of (score - reference) * scale * log2 e, keys beyond T
 // masked to -inf.  The chunking bounds the registers of a wave (<= 168), so
-// that 9 compute waves fit a compute unit and the lone last query of T = 257
-// does not cost a second pass; LDS fragments are fetched one step ahead of the
-// MFMAs using them.
+// that 12 waves fit a compute unit and the lone last query of T = 257 does not
+// cost a second pass; LDS fragments are fetched one step ahead of the MFMAs
+// using them.
 //
 // Template: DH = head width (multiple of 16), NKT = number of 32-key tiles the
 // LDS buffers hold (T <= 32*NKT, NKT a multiple of 3).
@@ -45,6 +47,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 
 constexpr int CH = 3;                              // 32-key tiles per chunk
+constexpr int NPROD = 3;                           // producer waves (staging only)
 
 template <int DH, int NKT>
 struct AttnShape {
@@ -59,7 +62,7 @@ struct AttnShape {
 };
 
 template <int DH, int NKT>
-__global__ __launch_bounds__(NKT * 64) void attn_bf16_kernel(const uint16_t *__restrict__ qkv,
+__global__ __launch_bounds__((NKT + NPROD) * 64) void attn_bf16_kernel(const uint16_t *__restrict__ qkv,
                                                              uint16_t *__restrict__ o, int T, int D,
                                                              int H, int n_pairs, float scale_log2e)
 {
@@ -77,8 +80,10 @@ __global__ __launch_bounds__(NKT * 64) void attn_bf16_kernel(const uint16_t *__r
     const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, g = lane >> 5;
     const size_t ld = (size_t)3 * D;
-    const int q0 = wave * 32;                                       // one wave per query tile
-    const bool has_tile = q0 < T;                                   // extra staging waves have none
+    // waves [0, nq) own one tile of 32 queries each; the NPROD waves after them only stage K and V
+    const int nq = (int)(blockDim.x >> 6) - NPROD;
+    const bool producer = wave >= nq;                               // wave-uniform
+    const int q0 = wave * 32;
 
     // Persistent workgroups: workgroup w sits on XCD w % 8 (round-robin dispatch).  Each XCD gets
     // a contiguous range of (image, head) pairs, so that the heads of an image, which share
@@ -95,68 +100,55 @@ __global__ __launch_bounds__(NKT * 64) void attn_bf16_kernel(const uint16_t *__r
     if (pair >= pair_end) return;                                   // whole workgroup
 
     // ---- staging: K row-major, V transposed (unit = 4 tokens x 8 components).  A round of the
-    // staging threads covers RPR token rows (K) or RPR groups of 4 tokens (V), 16 bytes per
+    // producer threads covers RPR token rows (K) or RPR groups of 4 tokens (V), 16 bytes per
     // thread and row; consecutive threads take consecutive 16-byte chunks of a row.  Tokens >= T
-    // lie past the end of the buffer descriptors and read as zeros.  The first SW waves, which
-    // by the oldest-first issue order finish their tiles first, fetch the next pair's K and V
-    // into registers while the others still compute; after the barrier that retires the
-    // current pair they write them to LDS.
-    constexpr int SW = NKT < 4 ? NKT : 4, ST = SW * 64;
+    // lie past the end of the buffer descriptors and read as zeros.  The producer waves issue
+    // the loads of the next pair's K and V when the query waves start on the current pair, hold
+    // them in registers, and write them to LDS after the barrier that retires the current pair.
+    constexpr int ST = NPROD * 64;
     constexpr int CPR = DH / 8, RPR = ST / CPR;
     constexpr int KB = (TP + RPR - 1) / RPR, VB = (TP / 4 + RPR - 1) / RPR;
     constexpr int OOB = 0x7FFFFFF0;
-    const bool stager = wave < SW;                                  // wave-uniform
+    const int ptid = tid - nq * 64;                                 // thread index among the producers
     uint4 kv[KB], vv[VB][4];
     bf16x8 qf[KSTEPS];
     const int row_bytes = (int)ld * 2;
     const int seg_bytes = (T - 1) * row_bytes + DH * 2;             // first to last byte of a head's q, k or v
 
-    auto fetch = [&](int p) {
-        const int b = p / H, h = p % H;
-        const uint16_t *img = qkv + (size_t)b * T * ld + (size_t)h * DH;
-        if (has_tile) {
-            // Q fragments (B operand: column = query l31, 8 consecutive components at 16*ks + 8*g)
-            const __amdgpu_buffer_rsrc_t q_rs =
-                __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(img), 0, seg_bytes, 0x00020000);
-            const int qrow = min(q0 + l31, T - 1);
+    // Q fragments of pair p (B operand: column = query l31, 8 consecutive components at 16*ks + 8*g)
+    auto fetch_q = [&](int p) {
+        const uint16_t *img = qkv + (size_t)(p / H) * T * ld + (size_t)(p % H) * DH;
+        const __amdgpu_buffer_rsrc_t q_rs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(img), 0, seg_bytes, 0x00020000);
+        const int qrow = min(q0 + l31, T - 1);
 #pragma unroll
-            for (int ks = 0; ks < KSTEPS; ++ks)
-                qf[ks] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
-                                                        q_rs, qrow * row_bytes + g * 16 + ks * 32, 0, 0));
-        }
-        if (!stager) {
-            // (fresh values on every path, so that nothing stays live across the tile computation)
+        for (int ks = 0; ks < KSTEPS; ++ks)
+            qf[ks] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(
+                                                    q_rs, qrow * row_bytes + g * 16 + ks * 32, 0, 0));
+    };
+    auto fetch_kv = [&](int p) {
+        const uint16_t *img = qkv + (size_t)(p / H) * T * ld + (size_t)(p % H) * DH;
+        const __amdgpu_buffer_rsrc_t k_rs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(img + D), 0, seg_bytes, 0x00020000);
+        const __amdgpu_buffer_rsrc_t v_rs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(img + 2 * D), 0, seg_bytes, 0x00020000);
+        const int r0 = ptid / CPR, c = ptid % CPR;
+        const int off0 = ptid < RPR * CPR ? r0 * row_bytes + c * 16 : OOB;
 #pragma unroll
-            for (int i = 0; i < KB; ++i) kv[i] = make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < KB; ++i)
+            kv[i] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                  k_rs, (int)((unsigned)off0 + (unsigned)(i * RPR * row_bytes)), 0, 0));
+        const int voff0 = ptid < RPR * CPR ? 4 * r0 * row_bytes + c * 16 : OOB;
 #pragma unroll
-            for (int i = 0; i < VB; ++i)
+        for (int i = 0; i < VB; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) vv[i][j] = make_uint4(0, 0, 0, 0);
-        } else {
-            const __amdgpu_buffer_rsrc_t k_rs =
-                __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(img + D), 0, seg_bytes, 0x00020000);
-            const __amdgpu_buffer_rsrc_t v_rs =
-                __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(img + 2 * D), 0, seg_bytes, 0x00020000);
-            int t = tid;
-            asm volatile("" : "+v"(t));       // recompute the offsets here rather than carry them through the loop
-            const int r0 = t / CPR, c = t % CPR;
-            const int off0 = t < RPR * CPR ? r0 * row_bytes + c * 16 : OOB;
-#pragma unroll
-            for (int i = 0; i < KB; ++i)
-                kv[i] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(
-                                                      k_rs, (int)((unsigned)off0 + (unsigned)(i * RPR * row_bytes)), 0, 0));
-            const int voff0 = t < RPR * CPR ? 4 * r0 * row_bytes + c * 16 : OOB;
-#pragma unroll
-            for (int i = 0; i < VB; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    vv[i][j] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(
-                                                             v_rs, (int)((unsigned)voff0 + (unsigned)((4 * i * RPR + j) * row_bytes)), 0, 0));
-        }
+            for (int j = 0; j < 4; ++j)
+                vv[i][j] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                         v_rs, (int)((unsigned)voff0 + (unsigned)((4 * i * RPR + j) * row_bytes)), 0, 0));
     };
     auto deposit = [&]() {
-        if (!stager || tid >= RPR * CPR) return;
-        const int r0 = tid / CPR, c = tid % CPR;
+        if (ptid >= RPR * CPR) return;
+        const int r0 = ptid / CPR, c = ptid % CPR;
 #pragma unroll
         for (int i = 0; i < KB; ++i)
             if ((i + 1) * RPR <= TP || r0 + i * RPR < TP)
@@ -182,7 +174,7 @@ __global__ __launch_bounds__(NKT * 64) void attn_bf16_kernel(const uint16_t *__r
         }
     };
 
-    fetch(pair);
+    if (producer) fetch_kv(pair); else fetch_q(pair);
     // rows DH .. ET*32-1 of V^T feed accumulator rows that are never stored: zeros, except that
     // rows DH and DH+4 hold ones when the MFMA is to deliver the softmax sum.  Written once.
     for (int id = tid; id < (ET * 32 - DH) * (TP / 4); id += nthr) {
@@ -191,12 +183,26 @@ __global__ __launch_bounds__(NKT * 64) void attn_bf16_kernel(const uint16_t *__r
         *reinterpret_cast<uint2 *>(Vt + e * VS + u4 * 4) = make_uint2(w, w);
     }
 
-    deposit();
+    if (producer) deposit();
     __syncthreads();
 
+    // Both roles run the same sequence of barriers: two per pair but the last.
+    if (producer) {
+        for (;;) {
+            const int next = pair + pair_step;
+            if (next >= pair_end) break;         // uniform over the workgroup
+            fetch_kv(next);                      // in flight while the query waves work on this pair
+            __syncthreads();                     // every query wave is done with this pair's K and V^T
+            deposit();
+            __syncthreads();
+            pair = next;
+        }
+        return;
+    }
     for (;;) {
     const int b = pair / H, h = pair % H;
-    if (has_tile) {
+    const int next = pair + pair_step;
+    const bool more = next < pair_end;           // uniform over the workgroup
 
     f32x16 ot[ET];
 #pragma unroll
@@ -336,13 +342,11 @@ __global__ __launch_bounds__(NKT * 64) void attn_bf16_kernel(const uint16_t *__r
                 }
             }
     }
-    }   // has_tile
-    pair += pair_step;
-    if (pair >= pair_end) break;             // uniform over the workgroup
-    fetch(pair);                             // in flight while the slower waves finish their tiles
-    __syncthreads();                         // every wave is done with the previous pair's K and V^T
-    deposit();
+    if (!more) break;
+    fetch_q(next);
     __syncthreads();
+    __syncthreads();
+    pair = next;
     }
 }
 
@@ -359,7 +363,7 @@ hipError_t launch_attn(const uint16_t *qkv, uint16_t *o, int B, int T, int D, in
         attr_set = true;
     }
     const int nq = (T + 31) / 32;          // one wave per tile of 32 queries, <= NKT
-    const int nw = std::max(nq, NKT < 4 ? NKT : 4);   // ... and at least the staging waves
+    const int nw = nq + NPROD;             // ... and the producer waves
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
     // one persistent workgroup per compute unit (the LDS footprint allows no more); a multiple
     // of 8 keeps the XCD-aware pair ranges
