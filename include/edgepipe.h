@@ -212,6 +212,23 @@ ep_status ep_partition(int32_t L, int32_t D, const double *t_comp, const double 
                        double *t_opt, int32_t *n_stages, int32_t *stage_dev,
                        int32_t *stage_first, int32_t *stage_last);
 
+/*
+ * The same problem, same inputs and the same answer, with identical devices
+ * collapsed into categories (section 3.3, after Algorithm 1: N categories of
+ * n_1 .. n_N identical devices shrink the search state from 2^D device subsets
+ * to prod (n_c + 1) count vectors).  Devices u, v are identical when
+ * t_comp[., u] == t_comp[., v], dev_mem[u] == dev_mem[v], bw[u][w] == bw[v][w]
+ * and bw[w][u] == bw[w][v] for every third device w, and bw[u][v] == bw[v][u];
+ * the categories are found from the inputs.  1 <= D <= 64; the table has
+ * L * prod (n_c + 1) * N entries (EP_ERR_OOM above 2^31).  T_opt and the
+ * strategy are bit for bit those of ep_partition on the same inputs.
+ * n_categories (HOST, may be NULL) receives N.
+ */
+ep_status ep_partition_categories(int32_t L, int32_t D, const double *t_comp, const double *layer_mem,
+                                  const double *dev_mem, const double *xfer_bytes, const double *bw,
+                                  double *t_opt, int32_t *n_stages, int32_t *stage_dev,
+                                  int32_t *stage_first, int32_t *stage_last, int32_t *n_categories);
+
 const char *ep_status_string(ep_status s);
 /* Text of the calling thread's most recent error ("" if none). */
 const char *ep_last_error(void);

@@ -68,12 +68,14 @@ def lib() -> C.CDLL:
         L.ep_stage_destroy.argtypes = [C.c_void_p]
         L.ep_stage_destroy.restype = None
         L.ep_partition.argtypes = [C.c_int32, C.c_int32, dp, dp, dp, dp, dp, dp, ip, ip, ip, ip]
+        L.ep_partition_categories.argtypes = [C.c_int32, C.c_int32, dp, dp, dp, dp, dp, dp, ip, ip, ip, ip, ip]
         L.ep_status_string.argtypes = [C.c_int]
         L.ep_status_string.restype = C.c_char_p
         L.ep_last_error.argtypes = []
         L.ep_last_error.restype = C.c_char_p
         for f in (L.ep_stage_create, L.ep_stage_forward, L.ep_stage_profile, L.ep_stage_trace_begin,
-                  L.ep_stage_trace_end, L.ep_stage_gemm_main_rows, L.ep_stage_device_bytes, L.ep_partition):
+                  L.ep_stage_trace_end, L.ep_stage_gemm_main_rows, L.ep_stage_device_bytes, L.ep_partition,
+                  L.ep_partition_categories):
             f.restype = C.c_int
         _lib = L
     return _lib
@@ -189,6 +191,31 @@ class Stage:
             self.destroy()
         except Exception:
             pass
+
+
+def partition_categories(t_comp, layer_mem, dev_mem, xfer_bytes, bw):
+    """ep_partition_categories.  Returns (T_opt, [(device, first_layer, last_layer), ...], n_categories)."""
+    t_comp = np.ascontiguousarray(t_comp, dtype=np.float64)
+    if t_comp.ndim != 2:
+        raise ValueError("t_comp must be [L, D]")
+    L, D = t_comp.shape
+    layer_mem = np.ascontiguousarray(layer_mem, dtype=np.float64)
+    dev_mem = np.ascontiguousarray(dev_mem, dtype=np.float64)
+    xfer_bytes = np.ascontiguousarray(xfer_bytes, dtype=np.float64)
+    bw = np.ascontiguousarray(bw, dtype=np.float64)
+    if layer_mem.shape != (L,) or xfer_bytes.shape != (L,) or dev_mem.shape != (D,) or bw.shape != (D, D):
+        raise ValueError("array shapes do not match t_comp [L, D]")
+    dp, ip = C.POINTER(C.c_double), C.POINTER(C.c_int32)
+    t_opt, n, ncat = C.c_double(), C.c_int32(), C.c_int32()
+    dev = np.zeros(D, dtype=np.int32)
+    first = np.zeros(D, dtype=np.int32)
+    last = np.zeros(D, dtype=np.int32)
+    _check(lib().ep_partition_categories(L, D, t_comp.ctypes.data_as(dp), layer_mem.ctypes.data_as(dp),
+                                         dev_mem.ctypes.data_as(dp), xfer_bytes.ctypes.data_as(dp),
+                                         bw.ctypes.data_as(dp), C.byref(t_opt), C.byref(n),
+                                         dev.ctypes.data_as(ip), first.ctypes.data_as(ip),
+                                         last.ctypes.data_as(ip), C.byref(ncat)), "ep_partition_categories")
+    return t_opt.value, [(int(dev[s]), int(first[s]), int(last[s])) for s in range(n.value)], int(ncat.value)
 
 
 def partition(t_comp, layer_mem, dev_mem, xfer_bytes, bw) -> Tuple[float, List[Tuple[int, int, int]]]:

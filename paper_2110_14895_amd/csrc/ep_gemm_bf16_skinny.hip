@@ -9,8 +9,8 @@
 // K split over up to 8 workgroups per tile (so that there are about two
 // workgroups per compute unit), and inside a workgroup the 16-wide K slices
 // dealt round-robin to its 8 waves.  A wave streams its slices straight from global memory into MFMA
-// fragments (no LDS staging: every byte is used once), up to six slices
-// (18 loads) in flight, and accumulates a private 64 x 32 partial.  The eight
+// fragments (no LDS staging: every byte is used once), up to ten slices
+// (30 loads) in flight, and accumulates a private 64 x 32 partial.  The eight
 // partials of a workgroup are summed through LDS in a fixed order (wave 0 .. 7).
 // Without a K split the workgroup then applies bias / GELU / residual and
 // stores; with one it writes its partial tile to a workspace and a second small
@@ -28,7 +28,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int TM = 64, TN = 32, NW = 8, U = 6, MAX_SPLIT = 8;
+constexpr int TM = 64, TN = 32, NW = 8, U = 10, MAX_SPLIT = 8;
 constexpr size_t SMEM = (size_t)NW * TM * TN * sizeof(float);
 
 template <int EPI>

@@ -282,6 +282,28 @@ def random_partition_instance(n_layers: int, n_devices: int, seed: int, *,
                              np.ascontiguousarray(bw))
 
 
+def category_partition_instance(n_layers: int, counts, seed: int, *, shuffle: bool = True,
+                                **kw) -> PartitionInstance:
+    """A cluster of N = len(counts) device types with counts[c] identical devices of type c
+    (section 3.3's setting for the category dynamic program): a random instance over the N types
+    is drawn with random_partition_instance and expanded per device; two devices of one type
+    are linked at that type's own diagonal bandwidth.  shuffle=True scatters the types over the
+    device ids (seeded), so that categories are not runs of consecutive ids."""
+    counts = [int(c) for c in counts]
+    N, D = len(counts), int(sum(counts))
+    base = random_partition_instance(n_layers, N, seed, **kw)
+    cat = np.repeat(np.arange(N), counts)
+    if shuffle:
+        order = np.argsort(uniform(f"part/cat{N}x{D}/order", D, seed), kind="stable")
+        cat = cat[order]
+    t_comp = np.ascontiguousarray(base.t_comp[:, cat])
+    dev_mem = base.dev_mem[cat].copy()
+    bw = np.ascontiguousarray(base.bw[np.ix_(cat, cat)])
+    # the diagonal of the type-level matrix is the link between two devices of one type; make it
+    # symmetric by construction (it is a single number per type)
+    return PartitionInstance(t_comp, base.layer_mem.copy(), dev_mem, base.xfer_bytes.copy(), bw)
+
+
 def heterogeneous_cluster(layer_cost_s: np.ndarray, shape: VitShape, batch: int, *,
                           n_devices: int = 16, seed: int = 1, act_bytes: int = 4,
                           param_bytes: int = 2,

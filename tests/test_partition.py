@@ -92,3 +92,82 @@ def test_removed_or_dead_device_is_not_selected():
     inst.bw[2, :] = 0.0                         # cannot send: only usable as the last stage
     _, s = binding.partition(*args(inst))
     assert 2 not in [d for d, _, _ in s[:-1]]
+
+
+# ------------------------------------------------------- categories of identical devices
+def test_categories_bit_exact_against_enumeration_and_naive_dp():
+    """Section 3.3: with identical devices collapsed into categories the optimum is unchanged.
+    Checked against exhaustive enumeration of the expanded per-device instance (the plain
+    definition) and against ep_partition, value and strategy, bit for bit."""
+    n_feasible = 0
+    shapes = [(6, (2, 1)), (5, (2, 2)), (6, (1, 1, 2)), (4, (3,)), (7, (2, 1, 1)), (5, (1, 3))]
+    kws = [dict(), dict(mem_tight=0.7), dict(comm_heavy=2.0), dict(mem_tight=0.5, comm_heavy=0.3, quantize=4),
+           dict(quantize=2)]
+    for seed in range(100):
+        L, counts = shapes[seed % len(shapes)]
+        inst = synth.category_partition_instance(L, counts, seed, **kws[seed % len(kws)])
+        bt, bs, _ = P.brute_force(*args(inst))
+        if bt is None:
+            with pytest.raises(binding.EdgePipeError) as ei:
+                binding.partition_categories(*args(inst))
+            assert ei.value.status == binding.EP_ERR_INFEASIBLE
+            continue
+        n_feasible += 1
+        t, s, ncat = binding.partition_categories(*args(inst))
+        assert ncat <= len(counts)          # (two types may coincide after quantisation)
+        assert t == bt and s == bs
+        assert (t, s) == binding.partition(*args(inst))
+    assert n_feasible > 20
+
+
+def test_categories_match_naive_dp_at_paper_scale():
+    # section 3.3's example: three device types with three devices each, ViT-Base (12 layers);
+    # then a larger cluster the subset program still handles, and distinct devices (N = D)
+    for L, counts, seed in [(12, (3, 3, 3), 0), (12, (3, 3, 3), 1), (24, (4, 4, 4, 3), 2), (16, (1,) * 10, 3),
+                            (12, (6, 6), 4)]:
+        for kw in (dict(), dict(mem_tight=0.8), dict(comm_heavy=1.0, quantize=3)):
+            inst = synth.category_partition_instance(L, counts, seed, **kw)
+            try:
+                ref = binding.partition(*args(inst))
+            except binding.EdgePipeError as e:
+                assert e.status == binding.EP_ERR_INFEASIBLE
+                with pytest.raises(binding.EdgePipeError):
+                    binding.partition_categories(*args(inst))
+                continue
+            t, s, ncat = binding.partition_categories(*args(inst))
+            assert (t, s) == ref
+            assert ncat <= len(counts)
+            assert P.evaluate(s, *args(inst)) == t
+
+
+def test_categories_handle_more_devices_than_the_subset_program():
+    # 3 types x 12 devices = 36 devices: 2^36 subsets are out of reach, 13^3 count vectors are not
+    inst = synth.category_partition_instance(24, (12, 12, 12), 5, mem_tight=0.9, shuffle=False)
+    t, s, ncat = binding.partition_categories(*args(inst))
+    assert ncat == 3
+    assert P.evaluate(s, *args(inst)) == t
+    assert s[0][1] == 0 and s[-1][2] == 23
+    assert all(s[k + 1][1] == s[k][2] + 1 for k in range(len(s) - 1))
+    assert len({d for d, _, _ in s}) == len(s)
+    # no single stage may beat the period, and using only one device of each type cannot be better
+    one_each = [int(np.flatnonzero(np.repeat(np.arange(3), 12) == c)[0]) for c in range(3)]
+    sub = synth.PartitionInstance(inst.t_comp[:, one_each], inst.layer_mem, inst.dev_mem[one_each],
+                                  inst.xfer_bytes, inst.bw[np.ix_(one_each, one_each)])
+    try:
+        t_sub, _ = binding.partition(*args(sub))
+        assert t <= t_sub
+    except binding.EdgePipeError as e:
+        assert e.status == binding.EP_ERR_INFEASIBLE
+
+
+def test_categories_detection_is_strict():
+    # a device that differs from its twin only in one link is a category of its own
+    inst = synth.category_partition_instance(6, (2, 2), 7, shuffle=False)
+    _, _, ncat = binding.partition_categories(*args(inst))
+    assert ncat == 2
+    inst.bw[0, 2] *= 1.5
+    t, s, ncat = binding.partition_categories(*args(inst))
+    assert ncat >= 3
+    assert (t, s) == binding.partition(*args(inst))
+    lib = binding.lib()
+    assert lib.ep_partition_categories(3, 65, None, None, None, None, None, None, None, None, None, None, None) == binding.EP_ERR_INVALID_ARG
