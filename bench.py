@@ -31,7 +31,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--model", default="vit_huge", help="vit_huge (headline) | vit_large | vit_base")
+    ap.add_argument("--model", default="vit_huge",
+                    help="vit_huge (headline) | vit_large | vit_base | deit_small | deit_tiny")
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--layers", type=int, default=0, help="0 = all layers of the model")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -108,7 +109,9 @@ def main() -> int:
                         "flop_per_launch": fl}
 
     result = {
-        "metric": "images/sec + % bf16 MFMA peak, ViT-Huge 32-layer encoder fwd, 1 MI355X",
+        "metric": ("images/sec + % bf16 MFMA peak, ViT-Huge 32-layer encoder fwd, 1 MI355X"
+                   if (sh.name, n_layers) == ("vit_huge", 32) else
+                   f"images/sec + % bf16 MFMA peak, {sh.name} {n_layers}-layer encoder fwd, 1 MI355X"),
         "value": round(images_per_s, 2), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",

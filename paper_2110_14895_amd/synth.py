@@ -181,6 +181,10 @@ SHAPES = {
     "vit_large": VitShape("vit_large", 24, 1024, 16, 4096, 197),
     # 224x224 image, patch 14, plus CLS
     "vit_huge": VitShape("vit_huge", 32, 1280, 16, 5120, 257),
+    # the smaller encoders of section 5.4 (DeiT-Tiny / -Small / -Base widths), 224x224 image,
+    # patch 16, plus CLS; 12 layers each, heads of 64
+    "deit_tiny": VitShape("deit_tiny", 12, 192, 3, 768, 197),
+    "deit_small": VitShape("deit_small", 12, 384, 6, 1536, 197),
 }
 
 

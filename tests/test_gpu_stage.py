@@ -209,6 +209,23 @@ def test_vit_huge_all_layers_batch_64_sampled_images():
         assert st.gemm_main_rows(64, kid) == 16384
 
 
+@pytest.mark.parametrize("name,batch", [("deit_tiny", 32), ("deit_small", 16), ("deit_small", 256)])
+def test_small_encoder_shapes_all_layers(name, batch):
+    # the narrow models of section 5.4: D = 192 / 384, 12 layers; small N and K stress the tile
+    # selection (N = 192 .. 1536) rather than the matrix pipe
+    sh = synth.SHAPES[name]
+    layers = layers_of(sh, sh.n_layers, bf16=True, affine=False)
+    st = H.make_stage(sh, layers, 0, sh.n_layers, batch, bf16=True)
+    x = synth.activations(sh, batch, bf16=True)
+    got = H.run_stage(st, x)
+    assert np.isfinite(got).all()
+    for i in sorted({0, batch - 1}):
+        ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x[i:i + 1])[0]
+        e = H.rel_err(got[i], ref)
+        print(f"{name} {sh.n_layers} layers B={batch} image {i}: err {e:.3e}, std {H.err_std(got[i], ref):.3e}")
+        assert e <= H.TOL_BF16
+
+
 # ------------------------------------------------- profiling, tracing, planning
 def test_profile_and_trace_report_positive_times():
     import torch
