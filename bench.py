@@ -35,6 +35,10 @@ def main() -> int:
                     help="vit_huge (headline) | vit_large | vit_base | deit_small | deit_tiny")
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--layers", type=int, default=0, help="0 = all layers of the model")
+    ap.add_argument("--stages", type=int, default=1,
+                    help="cut the layers evenly into this many pipeline stages (ep_pipeline_run) ...")
+    ap.add_argument("--micro-batch", type=int, default=0,
+                    help="... fed with micro-batches of this size (must divide --batch; default: the batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-split", action="store_true")
     args = ap.parse_args()
@@ -61,17 +65,40 @@ def main() -> int:
     x = synth.activations(sh, B, bf16=True)
     cfg = binding.VitConfig(sh.n_layers, sh.d_model, sh.n_heads, sh.d_mlp, sh.n_tokens, sh.ln_eps,
                             binding.EP_BF16, binding.EP_BF16, binding.EP_F32)
-    stage = binding.Stage(cfg, 0, n_layers, [synth.as_param_dtype(p, True) for p in layers], B)
     xin = torch.from_numpy(synth.f32_to_bf16_bits(x).reshape(x.shape).view(np.int16)).cuda()
     out = torch.empty(x.shape, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
+    mb = args.micro_batch or B
+    pipelined = args.stages > 1 or mb != B
+    if pipelined:
+        # the same work through the pipeline runtime: even cut into --stages stages, fp32 boundaries
+        if B % mb or args.stages > n_layers:
+            print("bench.py: --micro-batch must divide --batch and --stages must not exceed the layers", file=sys.stderr)
+            return 2
+        cuts = [round(k * n_layers / args.stages) for k in range(args.stages + 1)]
+        stages = []
+        for k in range(args.stages):
+            c = binding.VitConfig(sh.n_layers, sh.d_model, sh.n_heads, sh.d_mlp, sh.n_tokens, sh.ln_eps,
+                                  binding.EP_BF16, binding.EP_BF16 if k == 0 else binding.EP_F32, binding.EP_F32)
+            stages.append(binding.Stage(c, cuts[k], cuts[k + 1],
+                                        [synth.as_param_dtype(p, True) for p in layers[cuts[k]:cuts[k + 1]]], mb))
+        pipe = binding.Pipeline(stages, mb)
+        stage = None
+
+        def step():
+            pipe.run(xin, B // mb, out, stream)
+    else:
+        stage = binding.Stage(cfg, 0, n_layers, [synth.as_param_dtype(p, True) for p in layers], B)
+
+        def step():
+            stage.forward(xin, B, out, stream)
 
     for _ in range(args.warmup):
-        stage.forward(xin, B, out, stream)
+        step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        stage.forward(xin, B, out, stream)
+        step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -88,6 +115,8 @@ def main() -> int:
     kernels = {}
     fc1_main = binding.MAIN_KERNEL_IDS["fc1"]
     ids = list(range(len(binding.KERNEL_NAMES))) + [fc1_main] if not args.no_kernel_split else [fc1_main]
+    if pipelined:
+        ids = []           # the per-kernel split belongs to the single-stage run
     for kid in ids:
         steps = args.steps if kid == fc1_main else min(args.steps, 3)
         stage.trace_begin(kid, n_layers * steps)
@@ -117,7 +146,7 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{sh.name} {n_layers}-layer stage, micro-batch {B}, T={sh.n_tokens}, "
                                f"D={sh.d_model}, H={sh.n_heads}, M={sh.d_mlp}; bf16 in, fp32 residual and output",
-                   "micro_batch": B, "layers": n_layers},
+                   "micro_batch": mb, "layers": n_layers, "stages": args.stages, "batch": B},
         "tflops": round(tflops, 2), "frac_bf16_mfma_peak": round(tflops / PEAK_BF16_MFMA_TFLOPS, 4),
         "roofline": roofline,
         "kernel_us_per_launch": {k: (round(v, 2) if v else None) for k, v in kernels.items()},
@@ -138,7 +167,12 @@ def main() -> int:
         result["parity_image0_max_abs_over_rms"] = round(err, 5)
 
     print(json.dumps(result))
-    stage.destroy()
+    if pipelined:
+        pipe.destroy()
+        for st in stages:
+            st.destroy()
+    else:
+        stage.destroy()
     return 0
 
 

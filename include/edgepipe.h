@@ -176,12 +176,47 @@ ep_status ep_stage_trace_end(ep_stage_t *stage, int32_t *launches, double *secon
  */
 ep_status ep_stage_gemm_main_rows(const ep_stage_t *stage, int32_t B, int32_t kernel, int64_t *rows);
 
+/* Configuration, layer range and max_batch the stage was created with (HOST outputs,
+ * each may be NULL). */
+ep_status ep_stage_info(const ep_stage_t *stage, ep_vit_config *cfg, int32_t *layer_begin,
+                        int32_t *layer_end, int32_t *max_batch);
+
 /* Device bytes held by the stage (parameters + workspace). */
 ep_status ep_stage_device_bytes(const ep_stage_t *stage, uint64_t *bytes);
 
 /* Free the stage's device memory.  The caller must have synchronised any stream
  * that still runs its work.  NULL is allowed. */
 void ep_stage_destroy(ep_stage_t *stage);
+
+/*
+ * Pipeline of stages on this device (section 3.1: parts T_1 .. T_n of consecutive
+ * layers, micro-batches flowing through them; Eq. 2: the period is set by the
+ * slowest part).  The runtime of the paper minus the network: one stream per
+ * stage, two boundary buffers per stage boundary, events for "micro-batch m has
+ * left stage k" and for the reuse of a boundary buffer.
+ *
+ * ep_pipeline_create: `stages` (HOST array of n_stages handles, 1..64) in pipeline
+ * order; consecutive stages must cover consecutive layer ranges of the same
+ * width and token count, and the out_dtype of a stage must be the in_dtype of the
+ * next; every stage must have max_batch >= micro_batch.  The pipeline borrows the
+ * handles (the caller destroys them after the pipeline) and owns its streams,
+ * events and boundary buffers.
+ *
+ * ep_pipeline_run: x_in (DEVICE) holds n_micro micro-batches back to back,
+ * [n_micro * micro_batch, T, D] in the first stage's in_dtype; x_out (DEVICE)
+ * receives them in the last stage's out_dtype.  Enqueue only: the work is
+ * ordered after what `stream` holds at the call, and `stream` is made to wait
+ * for the last micro-batch; no host synchronisation.  Results are those of
+ * running the stages one after the other on each micro-batch.  A stage must
+ * not be used elsewhere while a run is in flight.  Streams have default priority.
+ */
+typedef struct ep_pipeline ep_pipeline_t;
+ep_status ep_pipeline_create(int32_t n_stages, ep_stage_t *const *stages, int32_t micro_batch,
+                             ep_pipeline_t **out);
+ep_status ep_pipeline_run(ep_pipeline_t *pipeline, const void *x_in, int32_t n_micro, void *x_out,
+                          void *stream);
+/* Synchronise the device (or at least `stream` of the last run) first.  NULL is allowed. */
+void ep_pipeline_destroy(ep_pipeline_t *pipeline);
 
 /*
  * Heterogeneity-aware optimal partition (sections 3.2-3.3), CPU only,

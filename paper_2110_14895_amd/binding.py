@@ -64,6 +64,11 @@ def lib() -> C.CDLL:
         L.ep_stage_trace_begin.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         L.ep_stage_trace_end.argtypes = [C.c_void_p, ip, dp]
         L.ep_stage_gemm_main_rows.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int64)]
+        L.ep_stage_info.argtypes = [C.c_void_p, C.POINTER(ep_vit_config), ip, ip, ip]
+        L.ep_pipeline_create.argtypes = [C.c_int32, C.POINTER(C.c_void_p), C.c_int32, C.POINTER(C.c_void_p)]
+        L.ep_pipeline_run.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.ep_pipeline_destroy.argtypes = [C.c_void_p]
+        L.ep_pipeline_destroy.restype = None
         L.ep_stage_device_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
         L.ep_stage_destroy.argtypes = [C.c_void_p]
         L.ep_stage_destroy.restype = None
@@ -75,7 +80,7 @@ def lib() -> C.CDLL:
         L.ep_last_error.restype = C.c_char_p
         for f in (L.ep_stage_create, L.ep_stage_forward, L.ep_stage_profile, L.ep_stage_trace_begin,
                   L.ep_stage_trace_end, L.ep_stage_gemm_main_rows, L.ep_stage_device_bytes, L.ep_partition,
-                  L.ep_partition_categories):
+                  L.ep_partition_categories, L.ep_stage_info, L.ep_pipeline_create, L.ep_pipeline_run):
             f.restype = C.c_int
         _lib = L
     return _lib
@@ -185,6 +190,33 @@ class Stage:
         if self._h:
             lib().ep_stage_destroy(self._h)
             self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+class Pipeline:
+    """ep_pipeline_*: stages on one device, micro-batches flowing through them on one stream per
+    stage.  Borrows the Stage objects (keep them alive; destroy the pipeline first)."""
+
+    def __init__(self, stages, micro_batch: int):
+        self._stages = list(stages)
+        arr = (C.c_void_p * len(self._stages))(*[st._h for st in self._stages])
+        h = C.c_void_p()
+        _check(lib().ep_pipeline_create(len(self._stages), arr, micro_batch, C.byref(h)), "ep_pipeline_create")
+        self._h = h
+        self.micro_batch = micro_batch
+
+    def run(self, x_in, n_micro: int, x_out, stream=None) -> None:
+        _check(lib().ep_pipeline_run(self._h, _addr(x_in), n_micro, _addr(x_out), _stream(stream)), "ep_pipeline_run")
+
+    def destroy(self) -> None:
+        if self._h:
+            lib().ep_pipeline_destroy(self._h)
+            self._h = None
 
     def __del__(self):
         try:

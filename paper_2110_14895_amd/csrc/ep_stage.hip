@@ -414,6 +414,17 @@ extern "C" ep_status ep_stage_gemm_main_rows(const ep_stage_t *st, int32_t B, in
     return EP_OK;
 }
 
+extern "C" ep_status ep_stage_info(const ep_stage_t *st, ep_vit_config *cfg, int32_t *layer_begin, int32_t *layer_end,
+                                   int32_t *max_batch)
+{
+    if (!st) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_info: null stage");
+    if (cfg) *cfg = st->cfg;
+    if (layer_begin) *layer_begin = st->begin;
+    if (layer_end) *layer_end = st->end;
+    if (max_batch) *max_batch = st->max_batch;
+    return EP_OK;
+}
+
 extern "C" ep_status ep_stage_device_bytes(const ep_stage_t *st, uint64_t *bytes)
 {
     if (!st || !bytes) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_device_bytes: null argument");
