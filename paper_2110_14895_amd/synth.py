@@ -344,6 +344,43 @@ def heterogeneous_cluster(layer_cost_s: np.ndarray, shape: VitShape, batch: int,
                              np.ascontiguousarray(bw))
 
 
+def surround_params(shape: VitShape, patch: int, channels: int, n_classes: int, seed: int = 0, *,
+                    bf16: bool = False, w_std: float = 0.02) -> Dict[str, np.ndarray]:
+    """float32 parameters of the patch embedding and of the classifier head for `shape`
+    (T = 1 + number of patches): w_patch [D, C*P*P], b_patch [D], cls [D], pos [T, D],
+    ln_g / ln_b [D] of the final LayerNorm, w_head [n_classes, D], b_head [n_classes].
+    Weights N(0, w_std), class token and position embeddings N(0, w_std), biases and LayerNorm
+    affine random so that every term shows; values bf16-representable if bf16."""
+    D, T = shape.d_model, shape.n_tokens
+    K = channels * patch * patch
+    tag = f"{shape.name}/surround"
+    p = {
+        "w_patch": (w_std * normal(tag + "/w_patch", D * K, seed)).reshape(D, K),
+        "b_patch": 0.1 * normal(tag + "/b_patch", D, seed),
+        "cls": w_std * normal(tag + "/cls", D, seed),
+        "pos": (w_std * normal(tag + "/pos", T * D, seed)).reshape(T, D),
+        "ln_g": 1.0 + 0.1 * normal(tag + "/ln_g", D, seed),
+        "ln_b": 0.1 * normal(tag + "/ln_b", D, seed),
+        "w_head": (w_std * normal(tag + "/w_head", n_classes * D, seed)).reshape(n_classes, D),
+        "b_head": 0.1 * normal(tag + "/b_head", n_classes, seed),
+    }
+    out = {}
+    for k, v in p.items():
+        v = v.astype(np.float32)
+        out[k] = round_to_bf16(v) if bf16 else v
+    return out
+
+
+def images(batch: int, channels: int, size: int, seed: int = 0, first_image: int = 0) -> np.ndarray:
+    """float32 [batch, channels, size, size] standard-normal pixels (normalised images), one
+    stream per image so that image i is the same in any batch."""
+    out = np.empty((batch, channels, size, size), dtype=np.float32)
+    for i in range(batch):
+        out[i] = normal(f"image/{channels}x{size}/{first_image + i}", channels * size * size, seed).reshape(
+            channels, size, size).astype(np.float32)
+    return out
+
+
 def as_param_dtype(params: Dict[str, np.ndarray], bf16: bool) -> Dict[str, np.ndarray]:
     """Host arrays in the storage type a stage is created from: bf16 bit
     patterns (uint16; the values must already be bf16-representable) or float32."""
