@@ -189,6 +189,59 @@ ep_status ep_stage_device_bytes(const ep_stage_t *stage, uint64_t *bytes);
 void ep_stage_destroy(ep_stage_t *stage);
 
 /*
+ * The parts around the encoder layers (section 4, "Deep Learning Models": the
+ * embedding layer brings the images to the uniform input of the transformer
+ * layers, which are what the paper partitions; model definition of the original
+ * ViT).  With a stage that holds all layers they map images to logits.
+ *
+ * Embedding: x[b, 0, :] = cls + pos[0]; x[b, 1+p, :] = patch_p . w_patch^T +
+ * b_patch + pos[1+p], patch p of the (image_size/patch)^2 grid in row-major
+ * order, its pixels flattened (channel, row, column) as a convolution weight
+ * [D, C, P, P] is.  T = 1 + (image_size/patch)^2 tokens.
+ * ep_embed_create: w_patch [D, C*P*P], b_patch [D], cls [D], pos [T, D], HOST, in
+ * param_dtype (bf16 bit patterns or fp32); copied.  param_dtype EP_BF16 runs the
+ * projection on the matrix cores (d_model % 64 == 0), EP_F32 in fp32 (then
+ * out_dtype must be EP_F32).  ep_embed_forward: images DEVICE fp32
+ * [B, C, image_size, image_size]; x_out DEVICE [B, T, D] in out_dtype, rounded
+ * once; enqueue only on `stream`.
+ */
+typedef struct {
+    int32_t image_size;  /* pixels per side */
+    int32_t patch;       /* P */
+    int32_t channels;    /* C */
+    int32_t d_model;     /* D */
+    int32_t param_dtype; /* ep_dtype of the host parameters */
+    int32_t out_dtype;   /* ep_dtype of x_out (the in_dtype of the first stage) */
+} ep_embed_config;
+typedef struct ep_embed ep_embed_t;
+ep_status ep_embed_create(const ep_embed_config *cfg, const void *w_patch, const void *b_patch,
+                          const void *cls, const void *pos, int32_t max_batch, ep_embed_t **out);
+ep_status ep_embed_forward(ep_embed_t *embed, const void *images, int32_t B, void *x_out, void *stream);
+void ep_embed_destroy(ep_embed_t *embed);
+
+/*
+ * Head: logits[b, :] = LayerNorm(x[b, 0, :]; ln_g, ln_b, ln_eps) . w_head^T +
+ * b_head: the final LayerNorm and the classifier act on the class-token row
+ * only.  ep_head_create: ln_g, ln_b [D], w_head [n_classes, D], b_head
+ * [n_classes], HOST, in param_dtype; copied.  EP_BF16 needs n_classes % 8 == 0,
+ * d_model % 16 == 0, max_batch <= 4096.  ep_head_forward: x DEVICE fp32
+ * [B, n_tokens, D] (the fp32 output of the last stage); logits DEVICE fp32
+ * [B, n_classes]; enqueue only on `stream`.
+ */
+typedef struct {
+    int32_t d_model;
+    int32_t n_tokens;
+    int32_t n_classes;
+    float ln_eps;
+    int32_t param_dtype;
+} ep_head_config;
+typedef struct ep_head ep_head_t;
+ep_status ep_head_create(const ep_head_config *cfg, const void *ln_g, const void *ln_b, const void *w_head,
+                         const void *b_head, int32_t max_batch, ep_head_t **out);
+ep_status ep_head_forward(ep_head_t *head, const void *x, int32_t B, void *logits, void *stream);
+void ep_head_destroy(ep_head_t *head);
+
+/*
  * Pipeline of stages on this device (section 3.1: parts T_1 .. T_n of consecutive
  * layers, micro-batches flowing through them; Eq. 2: the period is set by the
  * slowest part).  The runtime of the paper minus the network: one stream per

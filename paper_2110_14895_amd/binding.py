@@ -40,6 +40,16 @@ class ep_vit_config(C.Structure):
                 ("param_dtype", C.c_int32), ("in_dtype", C.c_int32), ("out_dtype", C.c_int32)]
 
 
+class ep_embed_config(C.Structure):
+    _fields_ = [("image_size", C.c_int32), ("patch", C.c_int32), ("channels", C.c_int32), ("d_model", C.c_int32),
+                ("param_dtype", C.c_int32), ("out_dtype", C.c_int32)]
+
+
+class ep_head_config(C.Structure):
+    _fields_ = [("d_model", C.c_int32), ("n_tokens", C.c_int32), ("n_classes", C.c_int32), ("ln_eps", C.c_float),
+                ("param_dtype", C.c_int32)]
+
+
 class ep_layer_weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in PARAM_NAMES]
 
@@ -69,6 +79,15 @@ def lib() -> C.CDLL:
         L.ep_pipeline_run.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.ep_pipeline_destroy.argtypes = [C.c_void_p]
         L.ep_pipeline_destroy.restype = None
+        vp = C.c_void_p
+        L.ep_embed_create.argtypes = [C.POINTER(ep_embed_config), vp, vp, vp, vp, C.c_int32, C.POINTER(vp)]
+        L.ep_embed_forward.argtypes = [vp, vp, C.c_int32, vp, vp]
+        L.ep_embed_destroy.argtypes = [vp]
+        L.ep_embed_destroy.restype = None
+        L.ep_head_create.argtypes = [C.POINTER(ep_head_config), vp, vp, vp, vp, C.c_int32, C.POINTER(vp)]
+        L.ep_head_forward.argtypes = [vp, vp, C.c_int32, vp, vp]
+        L.ep_head_destroy.argtypes = [vp]
+        L.ep_head_destroy.restype = None
         L.ep_stage_device_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
         L.ep_stage_destroy.argtypes = [C.c_void_p]
         L.ep_stage_destroy.restype = None
@@ -80,7 +99,8 @@ def lib() -> C.CDLL:
         L.ep_last_error.restype = C.c_char_p
         for f in (L.ep_stage_create, L.ep_stage_forward, L.ep_stage_profile, L.ep_stage_trace_begin,
                   L.ep_stage_trace_end, L.ep_stage_gemm_main_rows, L.ep_stage_device_bytes, L.ep_partition,
-                  L.ep_partition_categories, L.ep_stage_info, L.ep_pipeline_create, L.ep_pipeline_run):
+                  L.ep_partition_categories, L.ep_stage_info, L.ep_pipeline_create, L.ep_pipeline_run,
+                  L.ep_embed_create, L.ep_embed_forward, L.ep_head_create, L.ep_head_forward):
             f.restype = C.c_int
         _lib = L
     return _lib
@@ -190,6 +210,70 @@ class Stage:
         if self._h:
             lib().ep_stage_destroy(self._h)
             self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def _host(a: np.ndarray, param_dtype: int, name: str) -> np.ndarray:
+    want = np.uint16 if param_dtype == EP_BF16 else np.float32
+    a = np.ascontiguousarray(a)
+    if a.dtype != want:
+        raise TypeError(f"{name}: expected {np.dtype(want)} host array, got {a.dtype}")
+    return a
+
+
+class Embed:
+    """ep_embed_*: images [B, C, S, S] fp32 -> token sequence [B, T, D].  Host parameters in
+    param_dtype storage (uint16 bf16 bit patterns or float32): w_patch [D, C*P*P], b_patch [D],
+    cls [D], pos [T, D]."""
+
+    def __init__(self, image_size: int, patch: int, channels: int, d_model: int, param_dtype: int, out_dtype: int,
+                 params: Dict[str, np.ndarray], max_batch: int):
+        cfg = ep_embed_config(image_size, patch, channels, d_model, param_dtype, out_dtype)
+        keep = [_host(params[k], param_dtype, k) for k in ("w_patch", "b_patch", "cls", "pos")]
+        self._h = C.c_void_p()
+        _check(lib().ep_embed_create(C.byref(cfg), *[a.ctypes.data for a in keep], max_batch, C.byref(self._h)),
+               "ep_embed_create")
+        self.n_tokens = 1 + (image_size // patch) ** 2
+
+    def forward(self, images, batch: int, x_out, stream=None) -> None:
+        _check(lib().ep_embed_forward(self._h, _addr(images), batch, _addr(x_out), _stream(stream)), "ep_embed_forward")
+
+    def destroy(self) -> None:
+        if self._h:
+            lib().ep_embed_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+class Head:
+    """ep_head_*: x [B, T, D] fp32 -> logits [B, n_classes] fp32.  Host parameters ln_g, ln_b [D],
+    w_head [n_classes, D], b_head [n_classes] in param_dtype storage."""
+
+    def __init__(self, d_model: int, n_tokens: int, n_classes: int, ln_eps: float, param_dtype: int,
+                 params: Dict[str, np.ndarray], max_batch: int):
+        cfg = ep_head_config(d_model, n_tokens, n_classes, ln_eps, param_dtype)
+        keep = [_host(params[k], param_dtype, k) for k in ("ln_g", "ln_b", "w_head", "b_head")]
+        self._h = C.c_void_p()
+        _check(lib().ep_head_create(C.byref(cfg), *[a.ctypes.data for a in keep], max_batch, C.byref(self._h)),
+               "ep_head_create")
+
+    def forward(self, x, batch: int, logits, stream=None) -> None:
+        _check(lib().ep_head_forward(self._h, _addr(x), batch, _addr(logits), _stream(stream)), "ep_head_forward")
+
+    def destroy(self) -> None:
+        if self._h:
+            lib().ep_head_destroy(self._h)
+            self._h = None
 
     def __del__(self):
         try:

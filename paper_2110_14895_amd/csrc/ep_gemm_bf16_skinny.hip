@@ -1,7 +1,7 @@
 // bf16 MFMA GEMM for a short stack of rows (the remainder of M after the last
 // full 256-row tile of a dense layer, paper section 2.1):
 //
-//   C[M, N] = A[M, K] . W[N, K]^T + bias[N]   (+ erf GELU | + fp32 residual),  M small
+//   C[M, N] = A[M, K] . W[N, K]^T + bias[N]   (+ erf GELU | + fp32 residual | fp32 store),  M small
 //
 // Such a problem has few output tiles and a long K, so it is bound by latency
 // and by how many compute units pull the weights at once.  The work is cut
@@ -42,6 +42,8 @@ __device__ inline void store_epilogue(float v[4], const float *bias, const float
         const float4 x0 = *reinterpret_cast<const float4 *>(resid + off);
         float *C = reinterpret_cast<float *>(Cout);
         *reinterpret_cast<float4 *>(C + off) = make_float4(v[0] + x0.x, v[1] + x0.y, v[2] + x0.z, v[3] + x0.w);
+    } else if (EPI == EPI_BIAS_F32) {
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(Cout) + off) = make_float4(v[0], v[1], v[2], v[3]);
     } else {
         if (EPI == EPI_BIAS_GELU) {
 #pragma unroll
@@ -220,6 +222,7 @@ hipError_t ep_bf16_gemm_skinny(const uint16_t *A, const uint16_t *W, const float
     case EPI_BIAS: return launch_skinny<EPI_BIAS>(A, W, bias, resid, C, (int)M, N, K, ws, ws_floats, s);
     case EPI_BIAS_GELU: return launch_skinny<EPI_BIAS_GELU>(A, W, bias, resid, C, (int)M, N, K, ws, ws_floats, s);
     case EPI_BIAS_RESID: return launch_skinny<EPI_BIAS_RESID>(A, W, bias, resid, C, (int)M, N, K, ws, ws_floats, s);
+    case EPI_BIAS_F32: return launch_skinny<EPI_BIAS_F32>(A, W, bias, resid, C, (int)M, N, K, ws, ws_floats, s);
     }
     return hipErrorInvalidValue;
 }

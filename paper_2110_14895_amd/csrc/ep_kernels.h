@@ -10,7 +10,8 @@
 enum EpEpilogue {
     EPI_BIAS = 0,       // store (bf16 on the bf16 path, fp32 on the fp32 path)
     EPI_BIAS_GELU = 1,  // exact erf GELU, store
-    EPI_BIAS_RESID = 2  // add the fp32 residual, store fp32 (out may alias resid)
+    EPI_BIAS_RESID = 2, // add the fp32 residual, store fp32 (out may alias resid)
+    EPI_BIAS_F32 = 3    // store fp32 (short-M bf16 kernel only: the classifier's logits)
 };
 
 // ---- fp32 path -------------------------------------------------------------
