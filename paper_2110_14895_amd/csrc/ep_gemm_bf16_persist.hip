@@ -215,9 +215,12 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                 if (EPI == EPI_BIAS_RESID) {
                     // block [32 m][32 n] fp32: rows of 128 B = 8 chunks of 4 floats
                     float *C = reinterpret_cast<float *>(Cout);
+                    float4 bq[4];                    // the block's 32 bias values in one go: one wait, not four
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) bq[q] = bias4(nblk + q * 8);
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const float4 bb = bias4(nblk + q * 8);
+                        const float4 bb = bq[q];
                         const float4 v = make_float4(acc[ni][mi][q * 4 + 0] + bb.x, acc[ni][mi][q * 4 + 1] + bb.y,
                                                      acc[ni][mi][q * 4 + 2] + bb.z, acc[ni][mi][q * 4 + 3] + bb.w);
                         *reinterpret_cast<float4 *>(&stg[l31 * 8 + ((q * 2 + g) ^ (l31 & 7))]) = v;
@@ -241,9 +244,12 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                 } else {
                     // block [32 m][32 n] bf16: rows of 64 B = 4 chunks of 8 bf16
                     uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
+                    float4 bq[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) bq[q] = bias4(nblk + q * 8);
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
-                        const float4 bb = bias4(nblk + q * 8);
+                        const float4 bb = bq[q];
                         float v0 = acc[ni][mi][q * 4 + 0] + bb.x, v1 = acc[ni][mi][q * 4 + 1] + bb.y;
                         float v2 = acc[ni][mi][q * 4 + 2] + bb.z, v3 = acc[ni][mi][q * 4 + 3] + bb.w;
                         if (EPI == EPI_BIAS_GELU) {
