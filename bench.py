@@ -20,10 +20,10 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16
 # HBM bytes per launch of the dominant kernel at the headline workload, from two rocprofv3 --pmc
 # runs of this script (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the
-# input conversion kernel, whose traffic is known: 337.1 MB fetched + 171.0 MB written
+# input conversion kernel, whose traffic is known: 336.6 MB fetched + 170.1 MB written
 # (profiles/vit_huge_b64_fc1_hbm_traffic.md).  Valid for the kernel as profiled; set to None when
 # the kernel changes until the counters are taken again.
-FC1_MAIN_TRAFFIC_BYTES = 337.1e6 + 171.0e6
+FC1_MAIN_TRAFFIC_BYTES = 336.6e6 + 170.1e6
 
 
 def main() -> int:
