@@ -65,7 +65,11 @@ struct Tile {
     static constexpr int LDA = BM / 8 / NW, LDW = BN / 8 / NW;        // loads per wave per step (8 rows each)
     static constexpr size_t SMEM = (size_t)STAGES * STAGE_U4 * sizeof(uint4);
     static_assert(WM * WN == NW && BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BN % (8 * NW) == 0, "tile shape");
-    static_assert(LDA + LDW <= MI * NI, "one load per MFMA of the last slice");
+    // a step's loads are dealt over three slices (a burst of all of them holds every wave at the
+    // memory pipeline's door at once): [0, P0) in the last slice of the step before the previous one's
+    // end, [P0, P1) in slice 0 and [P1, LDA+LDW) in slice 1 of the step in between
+    static constexpr int P0 = 3, P1 = 6;
+    static_assert(P0 <= MI * NI && P1 - P0 <= MI * NI && LDA + LDW - P1 <= MI * NI && P1 < LDA + LDW, "one load per MFMA");
     static_assert(MI + NI <= MI * NI, "one fragment read per MFMA");
     static_assert(STAGE_U4 >= NW * 256, "a stage must hold 4 KB of epilogue staging per wave");
 };
@@ -87,6 +91,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int BN = T::BN, WN = T::WN, MI = T::MI, NI = T::NI;
     constexpr int A_STAGE = T::A_STAGE, STAGE_U4 = T::STAGE_U4, LDA = T::LDA, LDW = T::LDW;
+    constexpr int NLD = LDA + LDW, P0 = T::P0, P1 = T::P1;
     constexpr int NMFMA = MI * NI;
 
     extern __shared__ uint4 lds[];                   // [STAGES][A panel | W panel]
@@ -272,7 +277,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
         }
     };
 
-    // ---- prologue: step 0 into stage 0, wait, first fragments; then step 1 into stage 1
+    // ---- prologue: step 0 into stage 0, wait, first fragments; then the first loads of step 1 into stage 1
     set_load_tile(0);
 #pragma unroll
     for (int q = 0; q < LDA + LDW; ++q) issue_one(q);
@@ -283,35 +288,38 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 #pragma unroll
     for (int j = 0; j < NI + MI; ++j) read_frag(lds, 0, 0, j);
 #pragma unroll
-    for (int q = 0; q < LDA + LDW; ++q) issue_one(q);
-    advance_load();
+    for (int q = 0; q < P0; ++q) issue_one(q);
 
     int c_seq = 0, c_kt = 0;
     for (int it = 0; it < total_it; ++it) {
         const uint4 *cur = lds + (it & 1) * STAGE_U4;
         const uint4 *nxt = lds + ((it + 1) & 1) * STAGE_U4;
         const bool tile_end = c_kt == KT - 1;
-        // slices 0 .. NSL-2: multiply slice sl (buffer sl&1) while reading slice sl+1
+        // slices 0 .. NSL-2: multiply slice sl (buffer sl&1) while reading slice sl+1; slices 0 and 1
+        // also issue the rest of the next step's loads into the other stage
 #pragma unroll
         for (int sl = 0; sl < NSL - 1; ++sl) {
 #pragma unroll
             for (int q = 0; q < NMFMA; ++q) {
                 mfma_one(sl & 1, q);
                 if (q < NI + MI) read_frag(cur, sl + 1, (sl + 1) & 1, q);
+                if (sl == 0 && P0 + q < P1) issue_one(P0 + q);
+                if (sl == 1 && P1 + q < NLD) issue_one(P1 + q);
                 EP_SCHED_FENCE();
             }
         }
+        advance_load();
         // all my reads of this stage are done; the next step has landed; swap
         EP_WAIT_LGKMCNT0();
         EP_WAIT_VMCNT0();
         __builtin_amdgcn_s_barrier();
-        // last slice: read the next step's first fragments and refill the retired stage
-        // (at the end of a tile the stage first serves the epilogue and is refilled after it)
+        // last slice: read the next step's first fragments and start refilling the retired stage
+        // (at the end of a tile the stage first serves the epilogue and the refill starts after it)
 #pragma unroll
         for (int q = 0; q < NMFMA; ++q) {
             mfma_one((NSL - 1) & 1, q);
             if (q < NI + MI) read_frag(nxt, 0, 0, q);
-            if (q < LDA + LDW && !tile_end) issue_one(q);
+            if (q < P0 && !tile_end) issue_one(q);
             EP_SCHED_FENCE();
         }
         if (tile_end) {
@@ -324,11 +332,10 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
             EP_WAIT_LGKMCNT0();
             __builtin_amdgcn_s_barrier();           // every wave is done with the staging area
 #pragma unroll
-            for (int q = 0; q < LDA + LDW; ++q) issue_one(q);
+            for (int q = 0; q < P0; ++q) issue_one(q);
         } else {
             ++c_kt;
         }
-        advance_load();
     }
     EP_WAIT_VMCNT0();                               // drain the tail loads before LDS is released
 #endif
@@ -394,8 +401,8 @@ int64_t ep_bf16_gemm_persistent_cost(int64_t rows, int N, int *tile_bn)
 {
     const int cus = g_grid ? g_grid : 256;
     const int64_t c256 = tile_cost(rows, N, 256, cus), c320 = tile_cost(rows, N, 320, cus);
-    if (tile_bn) *tile_bn = c320 < c256 ? 320 : 256;
-    return c320 < c256 ? c320 : c256;
+    if (tile_bn) *tile_bn = c320 <= c256 ? 320 : 256;      // a tie goes to the wider tile (fewer bytes loaded per flop)
+    return c320 <= c256 ? c320 : c256;
 }
 
 // tile_bn: 0 = choose, else 256 or 320.  m_rows <= M: only rows [0, m_rows) are computed.
