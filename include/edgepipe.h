@@ -144,9 +144,10 @@ typedef enum {
     EP_K_COUNT = 7,
     /*
      * A dense layer may take two launches: one over the rows of whole 256-row
-     * tiles and a small one over the row remainder.  These ids time the first
-     * launch alone (bf16 path only; it is the whole layer when there is no second
-     * launch); ep_stage_gemm_main_rows gives the rows it covers.
+     * tiles (which, for short K, also takes the row remainder in its last phase)
+     * and, for long K, a small one over the row remainder.  These ids time the
+     * first launch alone (bf16 path only; it is the whole layer when there is no
+     * second launch); ep_stage_gemm_main_rows gives the rows it covers.
      */
     EP_K_QKV_MAIN = 7,
     EP_K_PROJ_MAIN = 8,

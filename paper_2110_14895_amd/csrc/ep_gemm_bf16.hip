@@ -262,7 +262,7 @@ hipError_t launch_epi(const uint16_t *A, const uint16_t *W, const float *bias, c
 
 }  // namespace
 
-int ep_bf16_gemm_num_configs() { return 17; }
+int ep_bf16_gemm_num_configs() { return 19; }
 
 hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, const float *bias,
                                const float *resid, void *C, int64_t M, int N, int K, int epi,
@@ -288,8 +288,8 @@ hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, co
     case 10: return launch_epi<128, 256, 32, 3, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     case 11: return launch_epi<128, 128, 32, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     case 12: return launch_epi<256, 128, 32, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 13: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 256, s);
-    case 14: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 320, s);
+    case 13: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 256, false, s);
+    case 14: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 320, false, s);
     case 15: return ep_bf16_gemm_skinny(A, W, bias, resid, C, M, N, K, epi, nullptr, 0, s);
     case 16: {
         // K-split variant; the sweep hook has no workspace argument, so it keeps one of its own
@@ -305,6 +305,16 @@ hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, co
         }
         return ep_bf16_gemm_skinny(A, W, bias, resid, C, M, N, K, epi, ws, ws_floats, s);
     }
+    case 17:   // the tile walk over the whole 256-row tiles, the remaining rows in the same launch
+        return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M / 256 * 256, N, K, epi, 0, true, s);
+    case 18: { // the same split as two launches, without a K split
+        const int64_t mm = M / 256 * 256;
+        hipError_t e = ep_bf16_gemm_persistent(A, W, bias, resid, C, M, mm, N, K, epi, 0, false, s);
+        if (e != hipSuccess || mm == M) return e;
+        const size_t csz = epi == EPI_BIAS_RESID ? 4 : 2;
+        return ep_bf16_gemm_skinny(A + mm * K, W, bias, resid ? resid + mm * N : nullptr,
+                                   (char *)C + (size_t)mm * N * csz, M - mm, N, K, epi, nullptr, 0, s);
+    }
     }
     return hipErrorInvalidValue;
 }
@@ -318,15 +328,17 @@ size_t ep_bf16_gemm_workspace_floats(int64_t M, int N)
 namespace {
 
 // How ep_bf16_gemm cuts the problem: rows [0, m_main) go to the persistent kernel with
-// tile width bn (bn = 0: the one-tile-per-workgroup kernel takes all rows), rows
-// [m_main, M) to the short-M kernel.
-struct GemmPlan { int64_t m_main; int bn; };
+// tile width bn (bn = 0: the one-tile-per-workgroup kernel takes all rows).  Rows [m_main, M)
+// are short-M work: with `fused` the persistent launch computes them after its tile walk,
+// otherwise the short-M kernel does (long K, where it pays to split K over more workgroups
+// than the tail phase of one launch can).
+struct GemmPlan { int64_t m_main; int bn; bool fused; };
 
 GemmPlan plan_gemm(int64_t M, int N, int K)
 {
     // At least one full round of 256-row tiles over the compute units: the persistent kernel.
     // If M leaves a short remainder after the last full tile and cutting it off saves a round,
-    // the remainder rows go to the short-M kernel.  Otherwise 128x128 tiles, two workgroups
+    // the remainder rows are short-M work.  Otherwise 128x128 tiles, two workgroups
     // per compute unit, which quantise better on small micro-batches.
     if (ep_bf16_gemm_persistent_supported(M, N, K)) {
         int bn_all = 0, bn_main = 0;
@@ -336,27 +348,31 @@ GemmPlan plan_gemm(int64_t M, int N, int K)
         if (tail > 0 && tail <= 128 && m_main > 0 && ep_bf16_gemm_skinny_supported(tail, N, K)) {
             const int64_t cost_main = ep_bf16_gemm_persistent_cost(m_main, N, &bn_main);
             const int64_t tiles_main = (m_main / 256) * ((N + bn_main - 1) / bn_main);
-            if (cost_main < cost_all && tiles_main >= 192) return {m_main, bn_main};
+            if (cost_main < cost_all && tiles_main >= 192) return {m_main, bn_main, K < 2560};
         }
-        if (tiles_all >= 192) return {M, bn_all};
+        if (tiles_all >= 192) return {M, bn_all, false};
     }
-    return {M, 0};
+    return {M, 0, false};
 }
 
 }  // namespace
 
-int64_t ep_bf16_gemm_main_rows(int64_t M, int N, int K) { return plan_gemm(M, N, K).m_main; }
+int64_t ep_bf16_gemm_main_rows(int64_t M, int N, int K)
+{
+    const GemmPlan p = plan_gemm(M, N, K);
+    return p.fused ? M : p.m_main;
+}
 
 hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
                         void *C, int64_t M, int N, int K, int epi, float *ws, size_t ws_floats,
                         hipEvent_t after_main, hipStream_t s)
 {
     const GemmPlan p = plan_gemm(M, N, K);
-    hipError_t e = p.bn ? ep_bf16_gemm_persistent(A, W, bias, resid, C, M, p.m_main, N, K, epi, p.bn, s)
+    hipError_t e = p.bn ? ep_bf16_gemm_persistent(A, W, bias, resid, C, M, p.m_main, N, K, epi, p.bn, p.fused, s)
                         : ep_bf16_gemm_config(3, A, W, bias, resid, C, M, N, K, epi, s);
     if (e != hipSuccess) return e;
     if (after_main && (e = hipEventRecord(after_main, s)) != hipSuccess) return e;
-    if (p.m_main == M) return hipSuccess;
+    if (p.m_main == M || p.fused) return hipSuccess;
     const size_t csz = epi == EPI_BIAS_RESID ? 4 : 2;
     return ep_bf16_gemm_skinny(A + p.m_main * K, W, bias, resid ? resid + p.m_main * N : nullptr,
                                (char *)C + (size_t)p.m_main * N * csz, M - p.m_main, N, K, epi, ws, ws_floats, s);

@@ -14,9 +14,11 @@
 //     L2 -> LDS path moves ~1.6x faster than half lines).  A step's A and W
 //     panels go from global memory straight into LDS with buffer_load ... lds
 //     (no register staging), two stages; the loads a wave issues per step are
-//     slipped one by one between the MFMAs of the step's last 16-wide slice,
-//     right after the barrier that retires the stage they overwrite, so they have
-//     a whole step to land.
+//     slipped one by one between MFMAs, dealt over three 16-wide slices: the
+//     first right after the barrier that retires the stage they overwrite, the
+//     rest in the first two slices of the following step (a burst of all of
+//     them holds every wave at the door of the memory pipeline at once); the
+//     last of them still has half a step to land.
 //   - LDS rows are 8 chunks of 16 bytes; chunk c of row r sits at slot
 //     c ^ f(r), f(r) = (r & 7) ^ ((r >> 3) & 1): the 16-byte fragment reads of 32
 //     consecutive rows are conflict-free on the 64-bank LDS.
@@ -38,10 +40,15 @@
 //
 // Requirements: K % 64 == 0, K >= 128, N % 8 == 0; M*K*2, N*K*2 < 2^31.  Rows
 // past M and columns past N are read as zeros (per-lane buffer offsets beyond
-// the end of the buffer) and never stored.  `m_rows` <= M limits the rows this
-// launch computes (the remaining rows are left to the caller).
+// the end of the buffer) and never stored.  `m_rows` <= M limits the rows the
+// tile walk computes.  The remaining rows are left to the caller, or, with
+// `fuse_tail`, computed in the same launch: after its last tile a workgroup
+// takes 64 x 32 tiles of rows [m_rows, M) (the short-M tile routine, K dealt to
+// the 8 waves, fixed-order sum through LDS), which saves the launch and ramp of
+// a second kernel when M is a few rows more than a multiple of 256.
 #include "ep_kernels.h"
 #include "ep_device.h"
+#include "ep_gemm_bf16_skinny_tile.h"
 
 namespace {
 
@@ -86,7 +93,7 @@ __device__ inline int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 template <class T, int EPI>
 __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const float *__restrict__ bias,
-    const float *resid, void *Cout, int M, int m_rows, int N, int K, int tiles_m, int tiles_n)
+    const float *resid, void *Cout, int M, int m_rows, int N, int K, int tiles_m, int tiles_n, int tail_rows)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int BN = T::BN, WN = T::WN, MI = T::MI, NI = T::NI;
@@ -106,8 +113,8 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
     const int G = gridDim.x;                         // multiple of 8
     const int total = tiles_m * tiles_n;
     const int first_id = (int)(blockIdx.x % NUM_XCD) * (G / NUM_XCD) + (int)(blockIdx.x / NUM_XCD);
-    if (first_id >= total) return;
-    const int n_my = (total - first_id + G - 1) / G;
+    if (first_id >= total && tail_rows == 0) return;
+    const int n_my = first_id < total ? (total - first_id + G - 1) / G : 0;
     const int KT = K / BK;
     const int total_it = n_my * KT;
 
@@ -338,6 +345,19 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
         }
     }
     EP_WAIT_VMCNT0();                               // drain the tail loads before LDS is released
+    // ---- rows [m_rows, m_rows + tail_rows): 64 x 32 tiles, dealt to the workgroups from the end of
+    // the tile order backwards (those are the ones with a tile less when the tiles do not divide)
+    if (tail_rows > 0) {
+        __syncthreads();
+        const int tn = (N + ep_skinny::TN - 1) / ep_skinny::TN;
+        const int units = tn * ((tail_rows + ep_skinny::TM - 1) / ep_skinny::TM);
+        for (int u = G - 1 - first_id; u < units; u += G) {
+            ep_skinny::tile<EPI>(A, W, bias, resid, Cout, nullptr, m_rows + tail_rows, N, K,
+                                 m_rows + (u / tn) * ep_skinny::TM, (u % tn) * ep_skinny::TN, 0, K,
+                                 reinterpret_cast<float *>(lds));
+            __syncthreads();
+        }
+    }
 #endif
 }
 
@@ -345,7 +365,7 @@ int g_grid = 0;
 
 template <class T, int EPI>
 hipError_t launch_persistent(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
-                             void *C, int M, int m_rows, int N, int K, hipStream_t s)
+                             void *C, int M, int m_rows, int N, int K, int tail_rows, hipStream_t s)
 {
     auto kern = gemm_bf16_persistent_kernel<T, EPI>;
     static bool attr_set = false;
@@ -365,18 +385,18 @@ hipError_t launch_persistent(const uint16_t *A, const uint16_t *W, const float *
     }
     const int tiles_m = (m_rows + BM - 1) / BM, tiles_n = (N + T::BN - 1) / T::BN;
     hipLaunchKernelGGL(kern, dim3(g_grid), dim3(NW * 64), T::SMEM, s, A, W, bias, resid, C, M, m_rows, N, K,
-                       tiles_m, tiles_n);
+                       tiles_m, tiles_n, tail_rows);
     return hipGetLastError();
 }
 
 template <class T>
 hipError_t launch_tile(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid, void *C,
-                       int M, int m_rows, int N, int K, int epi, hipStream_t s)
+                       int M, int m_rows, int N, int K, int epi, int tail_rows, hipStream_t s)
 {
     switch (epi) {
-    case EPI_BIAS: return launch_persistent<T, EPI_BIAS>(A, W, bias, resid, C, M, m_rows, N, K, s);
-    case EPI_BIAS_GELU: return launch_persistent<T, EPI_BIAS_GELU>(A, W, bias, resid, C, M, m_rows, N, K, s);
-    case EPI_BIAS_RESID: return launch_persistent<T, EPI_BIAS_RESID>(A, W, bias, resid, C, M, m_rows, N, K, s);
+    case EPI_BIAS: return launch_persistent<T, EPI_BIAS>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
+    case EPI_BIAS_GELU: return launch_persistent<T, EPI_BIAS_GELU>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
+    case EPI_BIAS_RESID: return launch_persistent<T, EPI_BIAS_RESID>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
     }
     return hipErrorInvalidValue;
 }
@@ -405,16 +425,18 @@ int64_t ep_bf16_gemm_persistent_cost(int64_t rows, int N, int *tile_bn)
     return c320 <= c256 ? c320 : c256;
 }
 
-// tile_bn: 0 = choose, else 256 or 320.  m_rows <= M: only rows [0, m_rows) are computed.
+// tile_bn: 0 = choose, else 256 or 320.  m_rows <= M: the tile walk covers rows [0, m_rows);
+// fuse_tail: rows [m_rows, M) are computed by the same launch as 64 x 32 tiles.
 hipError_t ep_bf16_gemm_persistent(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
                                    void *C, int64_t M, int64_t m_rows, int N, int K, int epi, int tile_bn,
-                                   hipStream_t s)
+                                   bool fuse_tail, hipStream_t s)
 {
     if (!ep_bf16_gemm_persistent_supported(M, N, K) || m_rows < 0 || m_rows > M) return hipErrorInvalidValue;
     if (epi == EPI_BIAS_RESID && !resid) return hipErrorInvalidValue;
     if (m_rows == 0) return hipSuccess;
+    const int tail = fuse_tail ? (int)(M - m_rows) : 0;
     if (tile_bn == 0) (void)ep_bf16_gemm_persistent_cost(m_rows, N, &tile_bn);
-    if (tile_bn == 320) return launch_tile<Tile320>(A, W, bias, resid, C, (int)M, (int)m_rows, N, K, epi, s);
-    if (tile_bn == 256) return launch_tile<Tile256>(A, W, bias, resid, C, (int)M, (int)m_rows, N, K, epi, s);
+    if (tile_bn == 320) return launch_tile<Tile320>(A, W, bias, resid, C, (int)M, (int)m_rows, N, K, epi, tail, s);
+    if (tile_bn == 256) return launch_tile<Tile256>(A, W, bias, resid, C, (int)M, (int)m_rows, N, K, epi, tail, s);
     return hipErrorInvalidValue;
 }

@@ -1,0 +1,131 @@
+// One 64 x 32 output tile of the short-M bf16 GEMM as a device function, shared by the short-M
+// kernel and by the tail phase of the persistent kernel (paper section 2.1: a dense layer of a
+// stage on the rows of a micro-batch):
+//
+//   C[m0 .. m0+63, n0 .. n0+31] = A[., k0 .. k0+kw) . W[., k0 .. k0+kw)^T  (+ bias, epilogue)
+//
+// The 16-wide K slices of [k0, k0+kw) are dealt round-robin to the 8 waves of the workgroup; a wave
+// streams its slices straight from global memory into MFMA fragments (no LDS staging: every byte is
+// used once), up to ten slices (30 loads) in flight, and accumulates a private 64 x 32 partial.  The
+// eight partials are summed through LDS in a fixed order (wave 0 .. 7), so the result does not depend
+// on timing.  Rows past M and columns past N are read as zeros (per-lane buffer offsets past the end)
+// and never stored.
+#pragma once
+#include "ep_kernels.h"
+#include "ep_device.h"
+
+namespace ep_skinny {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int TM = 64, TN = 32, NW = 8, U = 10;
+constexpr size_t SMEM = (size_t)NW * TM * TN * sizeof(float);      // 64 KB of LDS per workgroup
+
+template <int EPI>
+__device__ inline void store_epilogue(float v[4], const float *bias, const float *resid, void *Cout, int m, int n,
+                                      int N)
+{
+    const float4 b0 = *reinterpret_cast<const float4 *>(bias + n);
+    v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w;
+    const size_t off = (size_t)m * N + n;
+    if (EPI == EPI_BIAS_RESID) {
+        const float4 x0 = *reinterpret_cast<const float4 *>(resid + off);
+        float *C = reinterpret_cast<float *>(Cout);
+        *reinterpret_cast<float4 *>(C + off) = make_float4(v[0] + x0.x, v[1] + x0.y, v[2] + x0.z, v[3] + x0.w);
+    } else if (EPI == EPI_BIAS_F32) {
+        *reinterpret_cast<float4 *>(reinterpret_cast<float *>(Cout) + off) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+        if (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = gelu_erf(v[j]);
+        }
+        uint2 o;
+        o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]);
+        *reinterpret_cast<uint2 *>(reinterpret_cast<uint16_t *>(Cout) + off) = o;
+    }
+}
+
+// All 512 threads of the workgroup call this together.  part != nullptr: the raw partial tile goes to
+// part[m][n] (row stride N; the caller points it at its K split's slab) and no epilogue is applied.
+// lds: SMEM bytes, free on entry; the caller synchronises before it reuses them.
+template <int EPI>
+__device__ inline void tile(const uint16_t *__restrict__ A, const uint16_t *__restrict__ W,
+                            const float *__restrict__ bias, const float *resid, void *Cout,
+                            float *__restrict__ part, int M, int N, int K, int m0, int n0, int k0, int kw,
+                            float *lds)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    float (*wsum)[TM][TN] = reinterpret_cast<float (*)[TM][TN]>(lds);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l31 = lane & 31, g = lane >> 5;
+
+    const __amdgpu_buffer_rsrc_t a_rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(A), 0, (int)((size_t)M * K * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t w_rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(W), 0, (int)((size_t)N * K * 2), 0x00020000);
+    constexpr int OOB = 0x7FFFFFF0;
+    const int nsl = kw / 16;                         // slices of this tile; wave w takes w, w+8, ...
+    const int my_nsl = (nsl - wave + NW - 1) / NW;
+    // fragment f (0,1): rows f*32 + l31 of the tile, 8 elements at k + g*8
+    int a_off[2], w_off;
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+        const int am = m0 + f * 32 + l31;
+        a_off[f] = am < M ? (am * K + k0 + wave * 16 + g * 8) * 2 : OOB;
+    }
+    w_off = n0 + l31 < N ? ((n0 + l31) * K + k0 + wave * 16 + g * 8) * 2 : OOB;
+
+    f32x16 acc[2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[mi][i] = 0.f;
+
+    for (int s0 = 0; s0 < my_nsl; s0 += U) {
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 fa[U][2], fw[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool live = s0 + u < my_nsl;       // wave-uniform
+            const int ko = (s0 + u) * NW * 32;       // bytes: my slices are NW * 16 elements apart
+            fw[u] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(w_rs, live ? w_off + ko : OOB, 0, 0));
+#pragma unroll
+            for (int f = 0; f < 2; ++f)
+                fa[u][f] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(a_rs, live ? a_off[f] + ko : OOB, 0, 0));
+        }
+        __builtin_amdgcn_sched_barrier(0);           // all loads of the batch are issued before the first MFMA
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+                acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[u], fa[u][mi], acc[mi], 0, 0, 0);
+    }
+
+    // acc[mi][i] <-> column 8*(i/4) + 4*g + (i%4), row mi*32 + l31
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<float4 *>(&wsum[wave][mi * 32 + l31][q * 8 + g * 4]) =
+                make_float4(acc[mi][q * 4 + 0], acc[mi][q * 4 + 1], acc[mi][q * 4 + 2], acc[mi][q * 4 + 3]);
+    __syncthreads();
+
+    // thread t: row t/8, columns (t%8)*4 .. +3
+    const int r = tid >> 3, c = (tid & 7) * 4;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const float4 p0 = *reinterpret_cast<const float4 *>(&wsum[w][r][c]);
+        v[0] += p0.x; v[1] += p0.y; v[2] += p0.z; v[3] += p0.w;
+    }
+    const int m = m0 + r, n = n0 + c;
+    if (m < M && n < N) {
+        if (part) *reinterpret_cast<float4 *>(part + (size_t)m * N + n) = make_float4(v[0], v[1], v[2], v[3]);
+        else store_epilogue<EPI>(v, bias, resid, Cout, m, n, N);
+    }
+#endif
+}
+
+}  // namespace ep_skinny

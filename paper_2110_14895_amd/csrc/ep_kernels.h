@@ -52,14 +52,15 @@ hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, co
                                hipStream_t s);
 
 // persistent kernel for large problems (ep_gemm_bf16_persist.hip): 256 x BN tiles, BN = tile_bn
-// (256 or 320; 0 = pick the one with fewer weighted rounds).  Only rows [0, m_rows) are computed.
+// (256 or 320; 0 = pick the one with fewer weighted rounds).  The tile walk covers rows
+// [0, m_rows); with fuse_tail the same launch also computes rows [m_rows, M) as 64 x 32 tiles.
 bool ep_bf16_gemm_persistent_supported(int64_t M, int N, int K);
 // rounds of tiles over the compute units times the tile width (lower is better); writes the
 // tile width it would pick
 int64_t ep_bf16_gemm_persistent_cost(int64_t rows, int N, int *tile_bn);
 hipError_t ep_bf16_gemm_persistent(const uint16_t *A, const uint16_t *W, const float *bias,
                                    const float *resid, void *C, int64_t M, int64_t m_rows, int N,
-                                   int K, int epi, int tile_bn, hipStream_t s);
+                                   int K, int epi, int tile_bn, bool fuse_tail, hipStream_t s);
 
 // short-M kernel (ep_gemm_bf16_skinny.hip): 64 x 32 tiles, K split over workgroups (partials in
 // ws, summed by a second kernel) and over the 8 waves of a workgroup
