@@ -319,19 +319,12 @@ hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, co
     return hipErrorInvalidValue;
 }
 
-size_t ep_bf16_gemm_workspace_floats(int64_t M, int N)
-{
-    const int64_t tail = M % 256;                    // the only rows the short-M kernel ever gets
-    return tail > 0 && tail <= 128 ? ep_bf16_gemm_skinny_workspace_floats(tail, N) : 0;
-}
-
 namespace {
 
 // How ep_bf16_gemm cuts the problem: rows [0, m_main) go to the persistent kernel with
 // tile width bn (bn = 0: the one-tile-per-workgroup kernel takes all rows).  Rows [m_main, M)
 // are short-M work: with `fused` the persistent launch computes them after its tile walk,
-// otherwise the short-M kernel does (long K, where it pays to split K over more workgroups
-// than the tail phase of one launch can).
+// otherwise the short-M kernel does.
 struct GemmPlan { int64_t m_main; int bn; bool fused; };
 
 GemmPlan plan_gemm(int64_t M, int N, int K)
@@ -348,7 +341,7 @@ GemmPlan plan_gemm(int64_t M, int N, int K)
         if (tail > 0 && tail <= 128 && m_main > 0 && ep_bf16_gemm_skinny_supported(tail, N, K)) {
             const int64_t cost_main = ep_bf16_gemm_persistent_cost(m_main, N, &bn_main);
             const int64_t tiles_main = (m_main / 256) * ((N + bn_main - 1) / bn_main);
-            if (cost_main < cost_all && tiles_main >= 192) return {m_main, bn_main, K < 2560};
+            if (cost_main < cost_all && tiles_main >= 192) return {m_main, bn_main, true};
         }
         if (tiles_all >= 192) return {M, bn_all, false};
     }
@@ -364,8 +357,7 @@ int64_t ep_bf16_gemm_main_rows(int64_t M, int N, int K)
 }
 
 hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
-                        void *C, int64_t M, int N, int K, int epi, float *ws, size_t ws_floats,
-                        hipEvent_t after_main, hipStream_t s)
+                        void *C, int64_t M, int N, int K, int epi, hipEvent_t after_main, hipStream_t s)
 {
     const GemmPlan p = plan_gemm(M, N, K);
     hipError_t e = p.bn ? ep_bf16_gemm_persistent(A, W, bias, resid, C, M, p.m_main, N, K, epi, p.bn, p.fused, s)
@@ -375,5 +367,5 @@ hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias,
     if (p.m_main == M || p.fused) return hipSuccess;
     const size_t csz = epi == EPI_BIAS_RESID ? 4 : 2;
     return ep_bf16_gemm_skinny(A + p.m_main * K, W, bias, resid ? resid + p.m_main * N : nullptr,
-                               (char *)C + (size_t)p.m_main * N * csz, M - p.m_main, N, K, epi, ws, ws_floats, s);
+                               (char *)C + (size_t)p.m_main * N * csz, M - p.m_main, N, K, epi, nullptr, 0, s);
 }

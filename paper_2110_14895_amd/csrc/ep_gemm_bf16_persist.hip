@@ -43,9 +43,10 @@
 // the end of the buffer) and never stored.  `m_rows` <= M limits the rows the
 // tile walk computes.  The remaining rows are left to the caller, or, with
 // `fuse_tail`, computed in the same launch: after its last tile a workgroup
-// takes 64 x 32 tiles of rows [m_rows, M) (the short-M tile routine, K dealt to
-// the 8 waves, fixed-order sum through LDS), which saves the launch and ramp of
-// a second kernel when M is a few rows more than a multiple of 256.
+// takes narrow tiles of rows [m_rows, M) (the short-M tile routine: 64, 32 or
+// 16 rows by 32 columns, as narrow as it takes to give every workgroup one; K
+// dealt to the 8 waves, fixed-order sum through LDS), which saves the launch and
+// ramp of a second kernel when M is a few rows more than a multiple of 256.
 #include "ep_kernels.h"
 #include "ep_device.h"
 #include "ep_gemm_bf16_skinny_tile.h"
@@ -93,7 +94,7 @@ __device__ inline int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 template <class T, int EPI>
 __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const float *__restrict__ bias,
-    const float *resid, void *Cout, int M, int m_rows, int N, int K, int tiles_m, int tiles_n, int tail_rows)
+    const float *resid, void *Cout, int M, int m_rows, int N, int K, int tiles_m, int tiles_n, int tail_rows, int tail_tm)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int BN = T::BN, WN = T::WN, MI = T::MI, NI = T::NI;
@@ -345,16 +346,21 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
         }
     }
     EP_WAIT_VMCNT0();                               // drain the tail loads before LDS is released
-    // ---- rows [m_rows, m_rows + tail_rows): 64 x 32 tiles, dealt to the workgroups from the end of
-    // the tile order backwards (those are the ones with a tile less when the tiles do not divide)
+    // ---- rows [m_rows, m_rows + tail_rows): tail_tm x 32 tiles, dealt to the workgroups from the end
+    // of the tile order backwards (those are the ones with a tile less when the tiles do not divide)
     if (tail_rows > 0) {
         __syncthreads();
         const int tn = (N + ep_skinny::TN - 1) / ep_skinny::TN;
-        const int units = tn * ((tail_rows + ep_skinny::TM - 1) / ep_skinny::TM);
+        const int units = tn * ((tail_rows + tail_tm - 1) / tail_tm);
+        float *scratch = reinterpret_cast<float *>(lds);
         for (int u = G - 1 - first_id; u < units; u += G) {
-            ep_skinny::tile<EPI>(A, W, bias, resid, Cout, nullptr, m_rows + tail_rows, N, K,
-                                 m_rows + (u / tn) * ep_skinny::TM, (u % tn) * ep_skinny::TN, 0, K,
-                                 reinterpret_cast<float *>(lds));
+            const int tm0 = m_rows + (u / tn) * tail_tm, tn0 = (u % tn) * ep_skinny::TN;
+            if (tail_tm == 64)
+                ep_skinny::tile<EPI, 64>(A, W, bias, resid, Cout, nullptr, m_rows + tail_rows, N, K, tm0, tn0, 0, K, scratch);
+            else if (tail_tm == 32)
+                ep_skinny::tile<EPI, 32>(A, W, bias, resid, Cout, nullptr, m_rows + tail_rows, N, K, tm0, tn0, 0, K, scratch);
+            else
+                ep_skinny::tile16<EPI>(A, W, bias, resid, Cout, m_rows + tail_rows, N, K, tm0, tn0, scratch);
             __syncthreads();
         }
     }
@@ -362,6 +368,21 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 }
 
 int g_grid = 0;
+
+// Rows per tile (64, 32 or 16; all 32 columns wide) for the tail phase: the fewest rounds over the
+// workgroups, then the fewest bytes a workgroup pulls per tile (rows + 32 panel rows of K elements).
+int pick_tail_rows(int tail_rows, int N, int wgs)
+{
+    const int tn = (N + 31) / 32;
+    int best = 64;
+    int64_t best_cost = -1;
+    for (int tm : {64, 32, 16}) {
+        const int units = tn * ((tail_rows + tm - 1) / tm);
+        const int64_t cost = (int64_t)((units + wgs - 1) / wgs) * (tm + 32);
+        if (best_cost < 0 || cost < best_cost) { best = tm; best_cost = cost; }
+    }
+    return best;
+}
 
 template <class T, int EPI>
 hipError_t launch_persistent(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
@@ -385,7 +406,7 @@ hipError_t launch_persistent(const uint16_t *A, const uint16_t *W, const float *
     }
     const int tiles_m = (m_rows + BM - 1) / BM, tiles_n = (N + T::BN - 1) / T::BN;
     hipLaunchKernelGGL(kern, dim3(g_grid), dim3(NW * 64), T::SMEM, s, A, W, bias, resid, C, M, m_rows, N, K,
-                       tiles_m, tiles_n, tail_rows);
+                       tiles_m, tiles_n, tail_rows, tail_rows ? pick_tail_rows(tail_rows, N, g_grid) : 0);
     return hipGetLastError();
 }
 

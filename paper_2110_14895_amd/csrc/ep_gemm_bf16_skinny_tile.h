@@ -46,17 +46,20 @@ __device__ inline void store_epilogue(float v[4], const float *bias, const float
     }
 }
 
-// All 512 threads of the workgroup call this together.  part != nullptr: the raw partial tile goes to
-// part[m][n] (row stride N; the caller points it at its K split's slab) and no epilogue is applied.
+// All 512 threads of the workgroup call this together.  TMU = 64 or 32: rows of the tile (two or one
+// 32x32x16 MFMA blocks).  part != nullptr: the raw partial tile goes to part[m][n] (row stride N; the
+// caller points it at its K split's slab) and no epilogue is applied.
 // lds: SMEM bytes, free on entry; the caller synchronises before it reuses them.
-template <int EPI>
+template <int EPI, int TMU = TM>
 __device__ inline void tile(const uint16_t *__restrict__ A, const uint16_t *__restrict__ W,
                             const float *__restrict__ bias, const float *resid, void *Cout,
                             float *__restrict__ part, int M, int N, int K, int m0, int n0, int k0, int kw,
                             float *lds)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
-    float (*wsum)[TM][TN] = reinterpret_cast<float (*)[TM][TN]>(lds);
+    static_assert(TMU == 64 || TMU == 32, "tile rows");
+    constexpr int MI = TMU / 32;
+    float (*wsum)[TMU][TN] = reinterpret_cast<float (*)[TMU][TN]>(lds);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l31 = lane & 31, g = lane >> 5;
@@ -68,44 +71,44 @@ __device__ inline void tile(const uint16_t *__restrict__ A, const uint16_t *__re
     constexpr int OOB = 0x7FFFFFF0;
     const int nsl = kw / 16;                         // slices of this tile; wave w takes w, w+8, ...
     const int my_nsl = (nsl - wave + NW - 1) / NW;
-    // fragment f (0,1): rows f*32 + l31 of the tile, 8 elements at k + g*8
-    int a_off[2], w_off;
+    // fragment f: rows f*32 + l31 of the tile, 8 elements at k + g*8
+    int a_off[MI], w_off;
 #pragma unroll
-    for (int f = 0; f < 2; ++f) {
+    for (int f = 0; f < MI; ++f) {
         const int am = m0 + f * 32 + l31;
         a_off[f] = am < M ? (am * K + k0 + wave * 16 + g * 8) * 2 : OOB;
     }
     w_off = n0 + l31 < N ? ((n0 + l31) * K + k0 + wave * 16 + g * 8) * 2 : OOB;
 
-    f32x16 acc[2];
+    f32x16 acc[MI];
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[mi][i] = 0.f;
 
     for (int s0 = 0; s0 < my_nsl; s0 += U) {
         __builtin_amdgcn_sched_barrier(0);
-        bf16x8 fa[U][2], fw[U];
+        bf16x8 fa[U][MI], fw[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const bool live = s0 + u < my_nsl;       // wave-uniform
             const int ko = (s0 + u) * NW * 32;       // bytes: my slices are NW * 16 elements apart
             fw[u] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(w_rs, live ? w_off + ko : OOB, 0, 0));
 #pragma unroll
-            for (int f = 0; f < 2; ++f)
+            for (int f = 0; f < MI; ++f)
                 fa[u][f] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(a_rs, live ? a_off[f] + ko : OOB, 0, 0));
         }
         __builtin_amdgcn_sched_barrier(0);           // all loads of the batch are issued before the first MFMA
 #pragma unroll
         for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int mi = 0; mi < 2; ++mi)
+            for (int mi = 0; mi < MI; ++mi)
                 acc[mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[u], fa[u][mi], acc[mi], 0, 0, 0);
     }
 
     // acc[mi][i] <-> column 8*(i/4) + 4*g + (i%4), row mi*32 + l31
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
+    for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
         for (int q = 0; q < 4; ++q)
             *reinterpret_cast<float4 *>(&wsum[wave][mi * 32 + l31][q * 8 + g * 4]) =
@@ -114,16 +117,94 @@ __device__ inline void tile(const uint16_t *__restrict__ A, const uint16_t *__re
 
     // thread t: row t/8, columns (t%8)*4 .. +3
     const int r = tid >> 3, c = (tid & 7) * 4;
-    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (r < TMU) {
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
-        const float4 p0 = *reinterpret_cast<const float4 *>(&wsum[w][r][c]);
-        v[0] += p0.x; v[1] += p0.y; v[2] += p0.z; v[3] += p0.w;
+        for (int w = 0; w < NW; ++w) {
+            const float4 p0 = *reinterpret_cast<const float4 *>(&wsum[w][r][c]);
+            v[0] += p0.x; v[1] += p0.y; v[2] += p0.z; v[3] += p0.w;
+        }
+        const int m = m0 + r, n = n0 + c;
+        if (m < M && n < N) {
+            if (part) *reinterpret_cast<float4 *>(part + (size_t)m * N + n) = make_float4(v[0], v[1], v[2], v[3]);
+            else store_epilogue<EPI>(v, bias, resid, Cout, m, n, N);
+        }
     }
-    const int m = m0 + r, n = n0 + c;
-    if (m < M && n < N) {
-        if (part) *reinterpret_cast<float4 *>(part + (size_t)m * N + n) = make_float4(v[0], v[1], v[2], v[3]);
-        else store_epilogue<EPI>(v, bias, resid, Cout, m, n, N);
+#endif
+}
+
+// The same for a 16-row tile (16 x 32 outputs, two 16x16x32 MFMA blocks side by side): for long K and
+// few columns, where only narrow tiles give every compute unit one.  K is dealt in 32-wide slices.
+template <int EPI>
+__device__ inline void tile16(const uint16_t *__restrict__ A, const uint16_t *__restrict__ W,
+                              const float *__restrict__ bias, const float *resid, void *Cout, int M, int N, int K,
+                              int m0, int n0, float *lds)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    float (*wsum)[16][TN] = reinterpret_cast<float (*)[16][TN]>(lds);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l15 = lane & 15, g = lane >> 4;        // g: 8-element K group 0 .. 3 of a slice
+
+    const __amdgpu_buffer_rsrc_t a_rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(A), 0, (int)((size_t)M * K * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t w_rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(W), 0, (int)((size_t)N * K * 2), 0x00020000);
+    constexpr int OOB = 0x7FFFFFF0;
+    const int nsl = K / 32;                          // 32-wide slices; wave w takes w, w+8, ...
+    const int my_nsl = (nsl - wave + NW - 1) / NW;
+    const int am = m0 + l15;
+    const int a_off = am < M ? (am * K + wave * 32 + g * 8) * 2 : OOB;
+    int w_off[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int wn = n0 + j * 16 + l15;
+        w_off[j] = wn < N ? (wn * K + wave * 32 + g * 8) * 2 : OOB;
+    }
+
+    f32x4 acc[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[j][i] = 0.f;
+
+    for (int s0 = 0; s0 < my_nsl; s0 += U) {
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 fa[U], fw[U][2];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const bool live = s0 + u < my_nsl;       // wave-uniform
+            const int ko = (s0 + u) * NW * 64;       // bytes: my slices are NW * 32 elements apart
+            fa[u] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(a_rs, live ? a_off + ko : OOB, 0, 0));
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                fw[u][j] = __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(w_rs, live ? w_off[j] + ko : OOB, 0, 0));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fw[u][j], fa[u], acc[j], 0, 0, 0);
+    }
+
+    // acc[j][i] <-> column j*16 + 4*g + i, row l15
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+        *reinterpret_cast<float4 *>(&wsum[wave][l15][j * 16 + g * 4]) = make_float4(acc[j][0], acc[j][1], acc[j][2], acc[j][3]);
+    __syncthreads();
+
+    const int r = tid >> 3, c = (tid & 7) * 4;       // thread t: row t/8, columns (t%8)*4 .. +3
+    if (r < 16) {
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float4 p0 = *reinterpret_cast<const float4 *>(&wsum[w][r][c]);
+            v[0] += p0.x; v[1] += p0.y; v[2] += p0.z; v[3] += p0.w;
+        }
+        const int m = m0 + r, n = n0 + c;
+        if (m < M && n < N) store_epilogue<EPI>(v, bias, resid, Cout, m, n, N);
     }
 #endif
 }

@@ -28,14 +28,11 @@ hipError_t ep_bf16_layernorm(const float *x, const float *g, const float *b, flo
 hipError_t ep_bf16_to_f32(const uint16_t *in, float *out, int64_t n, hipStream_t s);
 hipError_t ep_f32_to_bf16(const float *in, uint16_t *out, int64_t n, hipStream_t s);
 // A bf16 [M, K], W bf16 [N, K]; out bf16 (EPI_BIAS, EPI_BIAS_GELU) or fp32 (EPI_BIAS_RESID).
-// ws: device scratch of ws_floats floats for the K-split partial sums of the short-M kernel
-// (ep_bf16_gemm_workspace_floats says how much serves a given problem; may be null: no K split).
 // after_main: if non-null, recorded on s right after the first launch (the rows
 // ep_bf16_gemm_main_rows reports), for timing that launch alone.
 hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias,
                         const float *resid, void *C, int64_t M, int N, int K, int epi,
-                        float *ws, size_t ws_floats, hipEvent_t after_main, hipStream_t s);
-size_t ep_bf16_gemm_workspace_floats(int64_t M, int N);
+                        hipEvent_t after_main, hipStream_t s);
 int64_t ep_bf16_gemm_main_rows(int64_t M, int N, int K);
 // qkv bf16 [B*T, 3D] -> o bf16 [B*T, D]
 hipError_t ep_bf16_attention(const uint16_t *qkv, uint16_t *o, int B, int T, int D, int H,

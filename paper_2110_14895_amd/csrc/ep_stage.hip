@@ -9,8 +9,6 @@
 //   x    fp32 [R, D]            residual stream
 //   a    act  [R, D]            LayerNorm output, later the attention output
 //   big  act  [R, max(3D, M)]   q|k|v, later the MLP hidden activations
-//   part fp32 [8, min(R, 128), max(3D, M)]   bf16 path only: K-split partial sums of the
-//                               GEMM kernel that takes the row remainder past the last 256-row tile
 // where act is bf16 on the bf16 path and fp32 on the fp32 path.
 #include <hip/hip_runtime.h>
 
@@ -54,8 +52,6 @@ struct ep_stage {
     float *x = nullptr;
     void *a = nullptr;
     void *big = nullptr;
-    float *part = nullptr;                 // K-split partial sums of the short-M GEMM
-    size_t part_floats = 0;
     std::vector<LayerDev> layers;
     // per-kernel timing (ep_stage_trace_begin / _end)
     int trace_kernel = -1;
@@ -141,19 +137,19 @@ ep_status run_layer(ep_stage *st, const LayerDev &L, const float *xin, float *xo
         uint16_t *a = (uint16_t *)st->a, *big = (uint16_t *)st->big;
         EP_TRACED(EP_K_LN1, ep_bf16_layernorm(xin, L.ln1_g, L.ln1_b, c.ln_eps, a, R, D, s));
         EP_TRACED_GEMM(EP_K_QKV, EP_K_QKV_MAIN,
-                       ep_bf16_gemm(a, (const uint16_t *)L.w_qkv, L.b_qkv, nullptr, big, R, 3 * D, D, EPI_BIAS, st->part,
-                                    st->part_floats, ts_.after_main(), s));
+                       ep_bf16_gemm(a, (const uint16_t *)L.w_qkv, L.b_qkv, nullptr, big, R, 3 * D, D, EPI_BIAS,
+                                    ts_.after_main(), s));
         EP_TRACED(EP_K_ATTN, ep_bf16_attention(big, a, B, T, D, H, s));
         EP_TRACED_GEMM(EP_K_PROJ, EP_K_PROJ_MAIN,
-                       ep_bf16_gemm(a, (const uint16_t *)L.w_o, L.b_o, xin, st->x, R, D, D, EPI_BIAS_RESID, st->part,
-                                    st->part_floats, ts_.after_main(), s));
+                       ep_bf16_gemm(a, (const uint16_t *)L.w_o, L.b_o, xin, st->x, R, D, D, EPI_BIAS_RESID,
+                                    ts_.after_main(), s));
         EP_TRACED(EP_K_LN2, ep_bf16_layernorm(st->x, L.ln2_g, L.ln2_b, c.ln_eps, a, R, D, s));
         EP_TRACED_GEMM(EP_K_FC1, EP_K_FC1_MAIN,
-                       ep_bf16_gemm(a, (const uint16_t *)L.w_fc1, L.b_fc1, nullptr, big, R, M, D, EPI_BIAS_GELU, st->part,
-                                    st->part_floats, ts_.after_main(), s));
+                       ep_bf16_gemm(a, (const uint16_t *)L.w_fc1, L.b_fc1, nullptr, big, R, M, D, EPI_BIAS_GELU,
+                                    ts_.after_main(), s));
         EP_TRACED_GEMM(EP_K_FC2, EP_K_FC2_MAIN,
-                       ep_bf16_gemm(big, (const uint16_t *)L.w_fc2, L.b_fc2, st->x, xout, R, D, M, EPI_BIAS_RESID, st->part,
-                                    st->part_floats, ts_.after_main(), s));
+                       ep_bf16_gemm(big, (const uint16_t *)L.w_fc2, L.b_fc2, st->x, xout, R, D, M, EPI_BIAS_RESID,
+                                    ts_.after_main(), s));
     } else {
         float *a = (float *)st->a, *big = (float *)st->big;
         EP_TRACED(EP_K_LN1, ep_f32_layernorm(xin, L.ln1_g, L.ln1_b, c.ln_eps, a, R, D, s));
@@ -226,10 +222,7 @@ extern "C" ep_status ep_stage_create(const ep_vit_config *cfg, int32_t layer_beg
     const size_t x_bytes = align_up(R * D * 4, 256);
     const size_t a_bytes = align_up(R * D * asz, 256);
     const size_t big_bytes = align_up(R * wide * asz, 256);
-    // any batch <= max_batch may leave a row remainder of up to 128 rows to the short-M GEMM
-    st->part_floats = st->bf16 ? ep_bf16_gemm_skinny_workspace_floats(R < 128 ? (int64_t)R : 128, (int)wide) : 0;
-    const size_t part_bytes = align_up(st->part_floats * sizeof(float), 256);
-    st->ws_bytes = x_bytes + a_bytes + big_bytes + part_bytes;
+    st->ws_bytes = x_bytes + a_bytes + big_bytes;
     e = hipMalloc((void **)&st->ws, st->ws_bytes);
     if (e != hipSuccess) {
         st->ws = nullptr;
@@ -239,7 +232,6 @@ extern "C" ep_status ep_stage_create(const ep_vit_config *cfg, int32_t layer_beg
     st->x = (float *)st->ws;
     st->a = st->ws + x_bytes;
     st->big = st->ws + x_bytes + a_bytes;
-    st->part = st->part_floats ? (float *)(st->ws + x_bytes + a_bytes + big_bytes) : nullptr;
 
     // ---- upload, one layer at a time through a host staging block
     std::vector<char> stage_buf;

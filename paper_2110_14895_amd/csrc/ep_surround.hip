@@ -135,9 +135,8 @@ struct ep_embed {
     char *mem = nullptr;
     size_t mem_bytes = 0;
     void *w = nullptr;          // [D, Kp] param dtype
-    float *b = nullptr, *cls = nullptr, *pos = nullptr, *posb = nullptr, *tmp = nullptr, *part = nullptr;
+    float *b = nullptr, *cls = nullptr, *pos = nullptr, *posb = nullptr, *tmp = nullptr;
     void *rows = nullptr;       // [max_batch*NP, Kp] param dtype
-    size_t part_floats = 0;
 };
 
 extern "C" void ep_embed_destroy(ep_embed_t *e)
@@ -183,12 +182,11 @@ extern "C" ep_status ep_embed_create(const ep_embed_config *cfg, const void *w_p
     const size_t R = (size_t)max_batch * e->NP;
     if (R * (size_t)(e->Kp > D ? e->Kp : D) >= (1ull << 31))
         return fail(ep_fail(EP_ERR_UNSUPPORTED, "ep_embed_create: max_batch %d is too large for this image size", max_batch));
-    e->part_floats = bf16 ? ep_bf16_gemm_skinny_workspace_floats(R < 128 ? (int64_t)R : 128, D) : 0;
 
     const size_t w_bytes = align_up((size_t)D * e->Kp * psz, 256), v_bytes = align_up((size_t)D * 4, 256);
     const size_t pos_bytes = align_up((size_t)e->T * D * 4, 256), big = align_up(R * D * 4, 256);
-    const size_t rows_bytes = align_up(R * e->Kp * psz, 256), part_bytes = align_up(e->part_floats * 4, 256);
-    e->mem_bytes = w_bytes + 2 * v_bytes + pos_bytes + 2 * big + rows_bytes + part_bytes;
+    const size_t rows_bytes = align_up(R * e->Kp * psz, 256);
+    e->mem_bytes = w_bytes + 2 * v_bytes + pos_bytes + 2 * big + rows_bytes;
     hipError_t he = hipMalloc((void **)&e->mem, e->mem_bytes);
     if (he != hipSuccess) {
         e->mem = nullptr;
@@ -201,8 +199,7 @@ extern "C" ep_status ep_embed_create(const ep_embed_config *cfg, const void *w_p
     e->pos = (float *)m; m += pos_bytes;
     e->posb = (float *)m; m += big;
     e->tmp = (float *)m; m += big;
-    e->rows = m; m += rows_bytes;
-    e->part = e->part_floats ? (float *)m : nullptr;
+    e->rows = m;
 
     // weight rows padded to Kp; vectors widened to fp32
     try {
@@ -251,7 +248,7 @@ extern "C" ep_status ep_embed_forward(ep_embed_t *e, const void *images, int32_t
                            (uint16_t *)e->rows, n_rows, c.channels, c.image_size, c.patch, e->G, e->K, e->Kp);
         EP_HIP(hipGetLastError());
         EP_HIP(ep_bf16_gemm((const uint16_t *)e->rows, (const uint16_t *)e->w, e->b, e->posb, e->tmp, R, D, e->Kp,
-                            EPI_BIAS_RESID, e->part, e->part_floats, nullptr, s));
+                            EPI_BIAS_RESID, nullptr, s));
     } else {
         hipLaunchKernelGGL(embed_gather_kernel<float>, dim3(blocks_for(n_rows)), dim3(256), 0, s, (const float *)images,
                            (float *)e->rows, n_rows, c.channels, c.image_size, c.patch, e->G, e->K, e->Kp);

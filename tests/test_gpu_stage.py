@@ -203,11 +203,10 @@ def test_vit_huge_all_layers_batch_64_sampled_images():
         assert e <= H.TOL_BF16
     rms = np.sqrt((got.astype(np.float64) ** 2).mean(axis=(1, 2)))
     assert np.all(np.abs(rms / rms[0] - 1) < 0.2)
-    # 64 * 257 rows = 64 tiles of 256 rows + 64: the dense layers with K = 1280 run as one
-    # persistent launch whose last phase takes the 64 remaining rows; the second MLP layer
-    # (K = 5120) runs the persistent launch over 16384 rows plus the short-M launch with its K split
+    # 64 * 257 rows = 64 tiles of 256 rows + 64: every dense layer runs as one persistent launch
+    # whose last phase takes the 64 remaining rows
     for name, kid in binding.MAIN_KERNEL_IDS.items():
-        assert st.gemm_main_rows(64, kid) == (16384 if name == "fc2" else 16448)
+        assert st.gemm_main_rows(64, kid) == 16448
 
 
 @pytest.mark.parametrize("name,batch", [("deit_tiny", 32), ("deit_small", 16), ("deit_small", 256)])
