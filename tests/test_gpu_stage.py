@@ -188,6 +188,29 @@ def test_vit_large_stage_of_six_layers_batch_sweep():
             assert np.all(np.abs(rms / rms[0] - 1) < 0.2)
 
 
+@pytest.mark.parametrize("B", [16, 32, 48])
+def test_vit_huge_row_remainder_shapes(B):
+    # B * 257 rows = B tiles of 256 rows + B rows: the dense layers that fill the chip take the B
+    # remaining rows (they belong to the last image) in the last phase of their launch, as tiles of
+    # 64, 32 or 16 rows depending on the layer's width; the narrower layers of the smaller batches
+    # run the one-tile-per-workgroup kernel instead
+    sh = synth.SHAPES["vit_huge"]
+    layers = layers_of(sh, 2, bf16=True, affine=True)
+    st = H.make_stage(sh, layers, 0, 2, B, bf16=True)
+    x = synth.activations(sh, B, bf16=True)
+    got = H.run_stage(st, x)
+    assert np.isfinite(got).all()
+    for i in (0, B - 1):
+        ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x[i:i + 1])[0]
+        e = H.rel_err(got[i], ref)
+        print(f"ViT-Huge 2 layers B={B} image {i}: err {e:.3e}")
+        assert e <= H.TOL_BF16
+        # the last rows of the last image are the remainder rows: check them on their own too
+        e_tail = H.rel_err(got[i][-B:], ref[-B:])
+        assert e_tail <= H.TOL_BF16
+    st.destroy()
+
+
 def test_vit_huge_all_layers_batch_64_sampled_images():
     # the benchmark configuration: 32 layers, B=64, T=257; the checker recomputes two images
     sh = synth.SHAPES["vit_huge"]
