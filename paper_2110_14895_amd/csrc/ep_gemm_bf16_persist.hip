@@ -28,8 +28,8 @@
 // Epilogue: 32 x 32 accumulator blocks (+bias, GELU) are transposed through the
 // LDS stage the tile's last step has just retired (4 KB per wave), so that
 // global stores and residual loads are whole row segments; the refill of that
-// stage for the next tile is issued right after.  Bias comes through the scalar
-// cache.
+// stage for the next tile is issued right after.  The tile's bias values wait
+// in LDS (loaded there during the K loop).
 //
 // Operand roles are swapped (MFMA A = W fragment, B = activation fragment) so
 // that a lane owns 4 consecutive output columns of one row.
@@ -71,7 +71,7 @@ struct Tile {
     static constexpr int A_STAGE = BM * CPR, W_STAGE = BN * CPR;      // uint4 per stage and operand
     static constexpr int STAGE_U4 = A_STAGE + W_STAGE;
     static constexpr int LDA = BM / 8 / NW, LDW = BN / 8 / NW;        // loads per wave per step (8 rows each)
-    static constexpr size_t SMEM = (size_t)STAGES * STAGE_U4 * sizeof(uint4);
+    static constexpr size_t SMEM = (size_t)(STAGES * STAGE_U4 + BN / 4) * sizeof(uint4);   // stages + the tile's bias
     static_assert(WM * WN == NW && BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BN % (8 * NW) == 0, "tile shape");
     // a step's loads are dealt over three slices (a burst of all of them holds every wave at the
     // memory pipeline's door at once): [0, P0) in the last slice of the step before the previous one's
@@ -204,16 +204,23 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
         acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][ni], fa[buf][mi], acc[ni][mi], 0, 0, 0);
     };
 
-    // bias[nb .. nb+7] through the scalar cache (nb is wave-uniform), so that the epilogue does not
-    // wait on the vector-memory counter; the lane keeps the half that belongs to its 4 columns
-    auto bias4 = [&](int nb) {
-        const int u = __builtin_amdgcn_readfirstlane(nb);
-        float lo0 = 0.f, lo1 = 0.f, lo2 = 0.f, lo3 = 0.f, hi0 = 0.f, hi1 = 0.f, hi2 = 0.f, hi3 = 0.f;
-        if (u < N) {                                 // N % 8 == 0: all eight or none
-            lo0 = bias[u + 0]; lo1 = bias[u + 1]; lo2 = bias[u + 2]; lo3 = bias[u + 3];
-            hi0 = bias[u + 4]; hi1 = bias[u + 5]; hi2 = bias[u + 6]; hi3 = bias[u + 7];
+    // The BN bias values of a tile sit in LDS behind the stages, brought there with 4-byte
+    // global -> LDS loads when the tile before it is stored (columns past N read as zeros), so the
+    // epilogue gets its lane's four values with one LDS read and no select between the halves of
+    // the wave; the loads ride on the K loop's own waits.
+    float *bias_lds = reinterpret_cast<float *>(lds + STAGES * STAGE_U4);
+    const __amdgpu_buffer_rsrc_t b_rs =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(bias), 0, N * 4, 0x00020000);
+    auto issue_bias = [&](int seq) {                 // wave w brings columns w*64 .. w*64+63 of tile seq
+        if (wave < BN / 64 && seq < n_my) {
+            int m0, n0;
+            tile_origin(seq, m0, n0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(b_rs, (lds_ptr)(bias_lds + wave * 64), 4, (n0 + wave * 64 + lane) * 4, 0,
+                                                     0, 0);
         }
-        return g ? make_float4(hi0, hi1, hi2, hi3) : make_float4(lo0, lo1, lo2, lo3);
+    };
+    auto bias4 = [&](int col) {                      // col: column inside the tile, a multiple of 8
+        return *reinterpret_cast<const float4 *>(bias_lds + col + 4 * g);
     };
 
     // ---- epilogue of the tile at (m0, n0); `stage` has just been retired and is free LDS.
@@ -230,7 +237,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                     float *C = reinterpret_cast<float *>(Cout);
                     float4 bq[4];                    // the block's 32 bias values in one go: one wait, not four
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) bq[q] = bias4(nblk + q * 8);
+                    for (int q = 0; q < 4; ++q) bq[q] = bias4(wn0 + ni * 32 + q * 8);
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const float4 bb = bq[q];
@@ -259,7 +266,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                     uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
                     float4 bq[4];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) bq[q] = bias4(nblk + q * 8);
+                    for (int q = 0; q < 4; ++q) bq[q] = bias4(wn0 + ni * 32 + q * 8);
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const float4 bb = bq[q];
@@ -290,6 +297,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 #pragma unroll
     for (int q = 0; q < LDA + LDW; ++q) issue_one(q);
     advance_load();
+    issue_bias(0);
     zero_acc();
     EP_WAIT_VMCNT0();
     __builtin_amdgcn_s_barrier();
@@ -338,7 +346,8 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
             c_kt = 0;
             ++c_seq;
             EP_WAIT_LGKMCNT0();
-            __builtin_amdgcn_s_barrier();           // every wave is done with the staging area
+            __builtin_amdgcn_s_barrier();           // every wave is done with the staging area and the bias
+            issue_bias(c_seq);
 #pragma unroll
             for (int q = 0; q < P0; ++q) issue_one(q);
         } else {
