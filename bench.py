@@ -20,10 +20,10 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16
 # HBM bytes per launch of the dominant kernel at the headline workload, from two rocprofv3 --pmc
 # runs of this script (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the
-# input conversion kernel, whose traffic is known: 336.6 MB fetched + 170.1 MB written
+# input conversion kernel, whose traffic is known: 308.2 MB fetched + 179.8 MB written
 # (profiles/vit_huge_b64_fc1_hbm_traffic.md).  Valid for the kernel as profiled; set to None when
 # the kernel changes until the counters are taken again.
-FC1_MAIN_TRAFFIC_BYTES = 336.6e6 + 170.1e6
+FC1_MAIN_TRAFFIC_BYTES = 308.2e6 + 179.8e6
 
 
 def main() -> int:
@@ -127,7 +127,7 @@ def main() -> int:
         if kid < len(binding.KERNEL_NAMES):
             kernels[binding.KERNEL_NAMES[kid]] = sec / n * 1e6 if n else None
         elif n:
-            rows = stage.gemm_main_rows(B, kid)          # rows this launch covers (whole 256-row tiles)
+            rows = stage.gemm_main_rows(B, kid)          # rows this launch covers
             fl = 2.0 * rows * sh.d_model * sh.d_mlp
             achieved = fl / (sec / n) / 1e12
             roofline = {"kernel": "fc1_gelu_gemm_main_launch", "bound": "mfma", "achieved": round(achieved, 2),
