@@ -318,6 +318,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 #pragma unroll
             for (int q = 0; q < NMFMA; ++q) {
                 mfma_one(sl & 1, q);
+                if (sl == 0 && q == 0) EP_SCHED_FENCE();    // the step's first MFMA waits for old reads only
                 if (q < NI + MI) read_frag(cur, sl + 1, (sl + 1) & 1, q);
                 if (sl == 0 && P0 + q < P1) issue_one(P0 + q);
                 if (sl == 1 && P1 + q < NLD) issue_one(P1 + q);
