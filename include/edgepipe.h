@@ -113,7 +113,11 @@ ep_status ep_stage_create(const ep_vit_config *cfg, int32_t layer_begin, int32_t
  *   x <- x + W_2 . gelu(W_1 . LN2(x) + b_1) + b_2
  * MHSA: per head, softmax over all T tokens of q.k / sqrt(d_head), no mask.
  * All work is enqueued on `stream` (a hipStream_t; NULL is the default stream);
- * the call does not allocate and does not synchronise.  1 <= B <= max_batch.
+ * the call does not allocate and does not synchronise, so it may be recorded in
+ * a stream capture once an earlier call on this device has run (the first call
+ * of a kernel sets a function attribute); while a trace is armed it also records
+ * events.  Calls on one stage share its workspace: do not overlap them.
+ * 1 <= B <= max_batch.
  */
 ep_status ep_stage_forward(ep_stage_t *stage, const void *x_in, int32_t B, void *x_out,
                            void *stream);

@@ -154,6 +154,39 @@ def test_determinism_and_workspace_poison():
     np.testing.assert_array_equal(a, b)
 
 
+def test_forward_under_graph_capture_replays_bit_exactly():
+    # ep_stage_forward only enqueues kernels on the caller's stream (no allocation, no
+    # synchronisation), so a caller may capture it in a graph: every replay, with eager work of
+    # the same stage in between, reproduces the eager result bit for bit.  Both dense-layer paths:
+    # persistent launches with a row remainder (ViT-Huge width, B = 16) and the small-tile kernel.
+    import torch
+    for sh, B in ((synth.custom_shape("bf_graph_small", 2, 320, 4, 640, 65), 3),
+                  (synth.custom_shape("bf_graph_wide", 1, 1280, 16, 5120, 257), 16)):
+        layers = layers_of(sh, sh.n_layers, bf16=True, w_std=0.05)
+        st = H.make_stage(sh, layers, 0, sh.n_layers, B, bf16=True)
+        x = synth.activations(sh, B, bf16=True)
+        other = synth.activations(sh, B, bf16=True, tag="other")
+        ref = H.run_stage(st, x)                                  # eager; also first-call set-up
+        xin, oin = H.to_device(x, True), H.to_device(other, True)
+        out = torch.empty(x.shape, dtype=torch.float32, device="cuda")
+        scratch = torch.empty_like(out)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                st.forward(xin, B, out, side)
+        for _ in range(3):
+            out.fill_(float("nan"))
+            st.forward(oin, B, scratch, torch.cuda.current_stream())   # eager work on the same workspace
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(out.cpu().numpy(), ref)
+        del graph
+        st.destroy()
+
+
 # ----------------------------------------------------- the named configurations
 def test_vit_base_stage_of_three_layers_batch_8():
     sh = synth.SHAPES["vit_base"]
