@@ -43,7 +43,7 @@ def main() -> int:
     ap.add_argument("--no-kernel-split", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (a pipeline stage is one device's work); "
+        print("bench.py: this library runs on one GPU only (a pipeline stage is one device's work); "
               "use --gpus 1", file=sys.stderr)
         return 2
 
