@@ -262,7 +262,9 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                                 make_float4(v[p].x + x[p].x, v[p].y + x[p].y, v[p].z + x[p].z, v[p].w + x[p].w);
                     }
                 } else {
-                    // block [32 m][32 n] bf16: rows of 64 B = 4 chunks of 8 bf16
+                    // block [32 m][32 n] bf16: rows of 64 B = 4 chunks of 8 bf16; chunk c of row r sits at slot
+                    // c ^ ((r >> 2) & 3): four rows span the 64 banks, so the 8-byte writes of 32 rows meet two to
+                    // a bank (the best a 64-byte row stride allows) and the 16-byte reads of 4 rows not at all
                     uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
                     float4 bq[4];
 #pragma unroll
@@ -278,13 +280,13 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                         uint2 o;
                         o.x = pack_bf16x2(v0, v1);
                         o.y = pack_bf16x2(v2, v3);
-                        reinterpret_cast<uint2 *>(&stg[l31 * 4 + (q ^ (l31 & 3))])[g] = o;
+                        reinterpret_cast<uint2 *>(&stg[l31 * 4 + (q ^ ((l31 >> 2) & 3))])[g] = o;
                     }
                     const int rrow = lane >> 2, rc = lane & 3;      // read-back: 16 rows x 4 chunks per pass
 #pragma unroll
                     for (int p = 0; p < 2; ++p) {
                         const int r = p * 16 + rrow, m = mblk + r, n = nblk + rc * 8;
-                        const uint4 v = stg[r * 4 + (rc ^ (r & 3))];
+                        const uint4 v = stg[r * 4 + (rc ^ ((r >> 2) & 3))];
                         if (m < m_rows && n < N) *reinterpret_cast<uint4 *>(C + (size_t)m * N + n) = v;
                     }
                 }
