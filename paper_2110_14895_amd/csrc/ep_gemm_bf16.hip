@@ -38,6 +38,7 @@
 // when that fills the chip; a remainder of at most 128 rows goes to the short-M
 // split-K kernel (ep_gemm_bf16_skinny.hip) when that lowers the number of tile
 // rounds; everything else runs here.
+#include <cstdint>
 #include "ep_kernels.h"
 #include "ep_device.h"
 
@@ -327,23 +328,37 @@ namespace {
 // otherwise the short-M kernel does.
 struct GemmPlan { int64_t m_main; int bn; bool fused; };
 
+// Cost of the tail phase in the units of ep_bf16_gemm_persistent_cost (a round of 256 x bn tiles
+// costs bn): a round of 64 x 32 tiles over the compute units takes about a tenth of a round of
+// 256 x 320 tiles of the same K (3-4 us against 36 us at K = 1280).
+int64_t tail_cost(int64_t tail_rows, int N)
+{
+    const int64_t units = ((tail_rows + 63) / 64) * ((N + 31) / 32);
+    return (units + 255) / 256 * 32;
+}
+
 GemmPlan plan_gemm(int64_t M, int N, int K)
 {
     // At least one full round of 256-row tiles over the compute units: the persistent kernel.
-    // If M leaves a short remainder after the last full tile and cutting it off saves a round,
-    // the remainder rows are short-M work.  Otherwise 128x128 tiles, two workgroups
-    // per compute unit, which quantise better on small micro-batches.
+    // The tile walk covers all rows, or stops one or two tile rows short of M and leaves the rest
+    // (at most 511 rows) to the tail phase of the same launch when that saves a round of tiles:
+    // a round of the narrow tail tiles is an order of magnitude cheaper.  Otherwise 128x128 tiles,
+    // two workgroups per compute unit, which quantise better on small micro-batches.
     if (ep_bf16_gemm_persistent_supported(M, N, K)) {
-        int bn_all = 0, bn_main = 0;
-        const int64_t m_main = M / 256 * 256, tail = M - m_main;
+        int bn_all = 0;
         const int64_t cost_all = ep_bf16_gemm_persistent_cost(M, N, &bn_all);
         const int64_t tiles_all = ((M + 255) / 256) * ((N + bn_all - 1) / bn_all);
-        if (tail > 0 && tail <= 128 && m_main > 0 && ep_bf16_gemm_skinny_supported(tail, N, K)) {
-            const int64_t cost_main = ep_bf16_gemm_persistent_cost(m_main, N, &bn_main);
+        GemmPlan best = {M, tiles_all >= 192 ? bn_all : 0, false};
+        int64_t best_cost = tiles_all >= 192 ? cost_all : INT64_MAX;
+        for (int64_t m_main = M / 256 * 256; m_main > 0 && M - m_main < 512; m_main -= 256) {
+            const int64_t tail = M - m_main;
+            if (tail == 0 || !ep_bf16_gemm_skinny_supported(tail, N, K)) continue;
+            int bn_main = 0;
+            const int64_t cost = ep_bf16_gemm_persistent_cost(m_main, N, &bn_main) + tail_cost(tail, N);
             const int64_t tiles_main = (m_main / 256) * ((N + bn_main - 1) / bn_main);
-            if (cost_main < cost_all && tiles_main >= 192) return {m_main, bn_main, true};
+            if (tiles_main >= 192 && cost < best_cost) { best = {m_main, bn_main, true}; best_cost = cost; }
         }
-        if (tiles_all >= 192) return {M, bn_all, false};
+        if (best.bn) return best;
     }
     return {M, 0, false};
 }
