@@ -39,6 +39,9 @@ def main() -> int:
                     help="cut the layers evenly into this many pipeline stages (ep_pipeline_run) ...")
     ap.add_argument("--micro-batch", type=int, default=0,
                     help="... fed with micro-batches of this size (must divide --batch; default: the batch)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time replays (pays off where the launches of a step, "
+                         "not its kernels, set the pace: narrow models, small batches)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-split", action="store_true")
     args = ap.parse_args()
@@ -70,6 +73,9 @@ def main() -> int:
     stream = torch.cuda.current_stream()
     mb = args.micro_batch or B
     pipelined = args.stages > 1 or mb != B
+    if pipelined and args.graph:
+        print("bench.py: --graph times the single-stage forward; drop --stages / --micro-batch", file=sys.stderr)
+        return 2
     if pipelined:
         # the same work through the pipeline runtime: even cut into --stages stages, fp32 boundaries
         if B % mb or args.stages > n_layers:
@@ -93,9 +99,21 @@ def main() -> int:
         def step():
             stage.forward(xin, B, out, stream)
 
-    for _ in range(args.warmup):
-        step()
+    for _ in range(max(args.warmup, 1) if args.graph else args.warmup):
+        step()                                   # also the first-call set-up, which a capture must not see
     torch.cuda.synchronize()
+    if args.graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        eager_stream, stream = stream, side
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        stream = eager_stream
+        step = graph.replay
+        step()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -115,8 +133,8 @@ def main() -> int:
     kernels = {}
     fc1_main = binding.MAIN_KERNEL_IDS["fc1"]
     ids = list(range(len(binding.KERNEL_NAMES))) + [fc1_main] if not args.no_kernel_split else [fc1_main]
-    if pipelined:
-        ids = []           # the per-kernel split belongs to the single-stage run
+    if pipelined or args.graph:
+        ids = []           # the per-kernel split belongs to the eager single-stage run
     for kid in ids:
         steps = args.steps if kid == fc1_main else min(args.steps, 3)
         stage.trace_begin(kid, n_layers * steps)
@@ -146,7 +164,8 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{sh.name} {n_layers}-layer stage, micro-batch {B}, T={sh.n_tokens}, "
                                f"D={sh.d_model}, H={sh.n_heads}, M={sh.d_mlp}; bf16 in, fp32 residual and output",
-                   "micro_batch": mb, "layers": n_layers, "stages": args.stages, "batch": B},
+                   "micro_batch": mb, "layers": n_layers, "stages": args.stages, "batch": B,
+                   "launch": "graph replay" if args.graph else "eager"},
         "tflops": round(tflops, 2), "frac_bf16_mfma_peak": round(tflops / PEAK_BF16_MFMA_TFLOPS, 4),
         "roofline": roofline,
         "kernel_us_per_launch": {k: (round(v, 2) if v else None) for k, v in kernels.items()},
