@@ -34,10 +34,10 @@
 // buffer offsets past the end of the buffer) and never stored.  K % 64 == 0 and
 // N % 8 == 0 required.
 //
-// Dispatcher: rows up to the last multiple of 256 go to the persistent kernel
-// when that fills the chip; a remainder of at most 128 rows goes to the short-M
-// split-K kernel (ep_gemm_bf16_skinny.hip) when that lowers the number of tile
-// rounds; everything else runs here.
+// Dispatcher: when 256-row tiles fill the chip the persistent kernel takes the
+// problem, its tile walk stopping up to two tile rows short of M when that saves
+// a round of tiles (the remaining rows are computed by the tail phase of the same
+// launch); everything else runs here.
 #include <cstdint>
 #include "ep_kernels.h"
 #include "ep_device.h"

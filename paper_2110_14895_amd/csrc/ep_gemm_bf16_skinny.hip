@@ -1,5 +1,6 @@
-// bf16 MFMA GEMM for a short stack of rows (the remainder of M after the last
-// full 256-row tile of a dense layer, paper section 2.1):
+// bf16 MFMA GEMM for a short stack of rows (a dense layer on few rows, paper
+// section 2.1: the classifier on the class tokens of a batch; the same tile
+// routine serves the row remainder inside the persistent kernel):
 //
 //   C[M, N] = A[M, K] . W[N, K]^T + bias[N]   (+ erf GELU | + fp32 residual | fp32 store),  M small
 //
