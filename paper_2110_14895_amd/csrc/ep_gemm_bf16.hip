@@ -263,7 +263,7 @@ hipError_t launch_epi(const uint16_t *A, const uint16_t *W, const float *bias, c
 
 }  // namespace
 
-int ep_bf16_gemm_num_configs() { return 19; }
+int ep_bf16_gemm_num_configs() { return 18; }
 
 hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, const float *bias,
                                const float *resid, void *C, int64_t M, int N, int K, int epi,
@@ -291,30 +291,16 @@ hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, co
     case 12: return launch_epi<256, 128, 32, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     case 13: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 256, false, s);
     case 14: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 320, false, s);
-    case 15: return ep_bf16_gemm_skinny(A, W, bias, resid, C, M, N, K, epi, nullptr, 0, s);
-    case 16: {
-        // K-split variant; the sweep hook has no workspace argument, so it keeps one of its own
-        static float *ws = nullptr;
-        static size_t ws_floats = 0;
-        const size_t need = ep_bf16_gemm_skinny_workspace_floats(M, N);
-        if (need > ws_floats) {
-            if (ws) (void)hipFree(ws);
-            ws = nullptr; ws_floats = 0;
-            hipError_t e = hipMalloc((void **)&ws, need * sizeof(float));
-            if (e != hipSuccess) return e;
-            ws_floats = need;
-        }
-        return ep_bf16_gemm_skinny(A, W, bias, resid, C, M, N, K, epi, ws, ws_floats, s);
-    }
-    case 17:   // the tile walk over the whole 256-row tiles, the remaining rows in the same launch
+    case 15: return ep_bf16_gemm_skinny(A, W, bias, resid, C, M, N, K, epi, s);
+    case 16:   // the tile walk over the whole 256-row tiles, the remaining rows in the same launch
         return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M / 256 * 256, N, K, epi, 0, true, s);
-    case 18: { // the same split as two launches, without a K split
+    case 17: { // the same split as two launches
         const int64_t mm = M / 256 * 256;
         hipError_t e = ep_bf16_gemm_persistent(A, W, bias, resid, C, M, mm, N, K, epi, 0, false, s);
         if (e != hipSuccess || mm == M) return e;
         const size_t csz = epi == EPI_BIAS_RESID ? 4 : 2;
         return ep_bf16_gemm_skinny(A + mm * K, W, bias, resid ? resid + mm * N : nullptr,
-                                   (char *)C + (size_t)mm * N * csz, M - mm, N, K, epi, nullptr, 0, s);
+                                   (char *)C + (size_t)mm * N * csz, M - mm, N, K, epi, s);
     }
     }
     return hipErrorInvalidValue;
@@ -382,5 +368,5 @@ hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias,
     if (p.m_main == M || p.fused) return hipSuccess;
     const size_t csz = epi == EPI_BIAS_RESID ? 4 : 2;
     return ep_bf16_gemm_skinny(A + p.m_main * K, W, bias, resid ? resid + p.m_main * N : nullptr,
-                               (char *)C + (size_t)p.m_main * N * csz, M - p.m_main, N, K, epi, nullptr, 0, s);
+                               (char *)C + (size_t)p.m_main * N * csz, M - p.m_main, N, K, epi, s);
 }

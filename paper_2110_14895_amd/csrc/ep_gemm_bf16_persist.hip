@@ -368,9 +368,9 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
         for (int u = G - 1 - first_id; u < units; u += G) {
             const int tm0 = m_rows + (u / tn) * tail_tm, tn0 = (u % tn) * ep_skinny::TN;
             if (tail_tm == 64)
-                ep_skinny::tile<EPI, 64>(A, W, bias, resid, Cout, nullptr, m_rows + tail_rows, N, K, tm0, tn0, 0, K, scratch);
+                ep_skinny::tile<EPI, 64>(A, W, bias, resid, Cout, m_rows + tail_rows, N, K, tm0, tn0, scratch);
             else if (tail_tm == 32)
-                ep_skinny::tile<EPI, 32>(A, W, bias, resid, Cout, nullptr, m_rows + tail_rows, N, K, tm0, tn0, 0, K, scratch);
+                ep_skinny::tile<EPI, 32>(A, W, bias, resid, Cout, m_rows + tail_rows, N, K, tm0, tn0, scratch);
             else
                 ep_skinny::tile16<EPI>(A, W, bias, resid, Cout, m_rows + tail_rows, N, K, tm0, tn0, scratch);
             __syncthreads();

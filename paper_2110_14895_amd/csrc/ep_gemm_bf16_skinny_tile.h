@@ -2,9 +2,9 @@
 // kernel and by the tail phase of the persistent kernel (paper section 2.1: a dense layer of a
 // stage on the rows of a micro-batch):
 //
-//   C[m0 .. m0+63, n0 .. n0+31] = A[., k0 .. k0+kw) . W[., k0 .. k0+kw)^T  (+ bias, epilogue)
+//   C[m0 .. m0+63, n0 .. n0+31] = A[m0 .. m0+63, :] . W[n0 .. n0+31, :]^T  (+ bias, epilogue)
 //
-// The 16-wide K slices of [k0, k0+kw) are dealt round-robin to the 8 waves of the workgroup; a wave
+// The 16-wide K slices are dealt round-robin to the 8 waves of the workgroup; a wave
 // streams its slices straight from global memory into MFMA fragments (no LDS staging: every byte is
 // used once), up to ten slices (30 loads) in flight, and accumulates a private 64 x 32 partial.  The
 // eight partials are summed through LDS in a fixed order (wave 0 .. 7), so the result does not depend
@@ -47,14 +47,11 @@ __device__ inline void store_epilogue(float v[4], const float *bias, const float
 }
 
 // All 512 threads of the workgroup call this together.  TMU = 64 or 32: rows of the tile (two or one
-// 32x32x16 MFMA blocks).  part != nullptr: the raw partial tile goes to part[m][n] (row stride N; the
-// caller points it at its K split's slab) and no epilogue is applied.
-// lds: SMEM bytes, free on entry; the caller synchronises before it reuses them.
+// 32x32x16 MFMA blocks).  lds: SMEM bytes, free on entry; the caller synchronises before it reuses them.
 template <int EPI, int TMU = TM>
 __device__ inline void tile(const uint16_t *__restrict__ A, const uint16_t *__restrict__ W,
-                            const float *__restrict__ bias, const float *resid, void *Cout,
-                            float *__restrict__ part, int M, int N, int K, int m0, int n0, int k0, int kw,
-                            float *lds)
+                            const float *__restrict__ bias, const float *resid, void *Cout, int M, int N, int K,
+                            int m0, int n0, float *lds)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     static_assert(TMU == 64 || TMU == 32, "tile rows");
@@ -69,16 +66,16 @@ __device__ inline void tile(const uint16_t *__restrict__ A, const uint16_t *__re
     const __amdgpu_buffer_rsrc_t w_rs =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(W), 0, (int)((size_t)N * K * 2), 0x00020000);
     constexpr int OOB = 0x7FFFFFF0;
-    const int nsl = kw / 16;                         // slices of this tile; wave w takes w, w+8, ...
+    const int nsl = K / 16;                          // slices of this tile; wave w takes w, w+8, ...
     const int my_nsl = (nsl - wave + NW - 1) / NW;
     // fragment f: rows f*32 + l31 of the tile, 8 elements at k + g*8
     int a_off[MI], w_off;
 #pragma unroll
     for (int f = 0; f < MI; ++f) {
         const int am = m0 + f * 32 + l31;
-        a_off[f] = am < M ? (am * K + k0 + wave * 16 + g * 8) * 2 : OOB;
+        a_off[f] = am < M ? (am * K + wave * 16 + g * 8) * 2 : OOB;
     }
-    w_off = n0 + l31 < N ? ((n0 + l31) * K + k0 + wave * 16 + g * 8) * 2 : OOB;
+    w_off = n0 + l31 < N ? ((n0 + l31) * K + wave * 16 + g * 8) * 2 : OOB;
 
     f32x16 acc[MI];
 #pragma unroll
@@ -125,10 +122,7 @@ __device__ inline void tile(const uint16_t *__restrict__ A, const uint16_t *__re
             v[0] += p0.x; v[1] += p0.y; v[2] += p0.z; v[3] += p0.w;
         }
         const int m = m0 + r, n = n0 + c;
-        if (m < M && n < N) {
-            if (part) *reinterpret_cast<float4 *>(part + (size_t)m * N + n) = make_float4(v[0], v[1], v[2], v[3]);
-            else store_epilogue<EPI>(v, bias, resid, Cout, m, n, N);
-        }
+        if (m < M && n < N) store_epilogue<EPI>(v, bias, resid, Cout, m, n, N);
     }
 #endif
 }

@@ -59,10 +59,8 @@ hipError_t ep_bf16_gemm_persistent(const uint16_t *A, const uint16_t *W, const f
                                    const float *resid, void *C, int64_t M, int64_t m_rows, int N,
                                    int K, int epi, int tile_bn, bool fuse_tail, hipStream_t s);
 
-// short-M kernel (ep_gemm_bf16_skinny.hip): 64 x 32 tiles, K split over workgroups (partials in
-// ws, summed by a second kernel) and over the 8 waves of a workgroup
+// short-M kernel (ep_gemm_bf16_skinny.hip): 64 x 32 tiles, K dealt to the 8 waves of a workgroup
 bool ep_bf16_gemm_skinny_supported(int64_t M, int N, int K);
-size_t ep_bf16_gemm_skinny_workspace_floats(int64_t M, int N);
 hipError_t ep_bf16_gemm_skinny(const uint16_t *A, const uint16_t *W, const float *bias,
                                const float *resid, void *C, int64_t M, int N, int K, int epi,
-                               float *ws, size_t ws_floats, hipStream_t s);
+                               hipStream_t s);

@@ -274,9 +274,8 @@ struct ep_head {
     char *mem = nullptr;
     size_t mem_bytes = 0;
     void *w = nullptr;          // [n_classes, D] param dtype
-    float *b = nullptr, *g = nullptr, *beta = nullptr, *rows = nullptr, *part = nullptr;
+    float *b = nullptr, *g = nullptr, *beta = nullptr, *rows = nullptr;
     void *z = nullptr;          // [max_batch, D] LayerNorm output, param dtype
-    size_t part_floats = 0;
 };
 
 extern "C" void ep_head_destroy(ep_head_t *h)
@@ -309,11 +308,10 @@ extern "C" ep_status ep_head_create(const ep_head_config *cfg, const void *ln_g,
     if (hipGetDevice(&h->device) != hipSuccess) return fail(ep_fail(EP_ERR_HIP, "hipGetDevice failed"));
     const int D = cfg->d_model, NC = cfg->n_classes;
     const size_t psz = bf16 ? 2 : 4;
-    h->part_floats = bf16 ? ep_bf16_gemm_skinny_workspace_floats(max_batch, NC) : 0;
     const size_t w_bytes = align_up((size_t)NC * D * psz, 256), b_bytes = align_up((size_t)NC * 4, 256);
     const size_t v_bytes = align_up((size_t)D * 4, 256), rows_bytes = align_up((size_t)max_batch * D * 4, 256);
-    const size_t z_bytes = align_up((size_t)max_batch * D * psz, 256), part_bytes = align_up(h->part_floats * 4, 256);
-    h->mem_bytes = w_bytes + b_bytes + 2 * v_bytes + rows_bytes + z_bytes + part_bytes;
+    const size_t z_bytes = align_up((size_t)max_batch * D * psz, 256);
+    h->mem_bytes = w_bytes + b_bytes + 2 * v_bytes + rows_bytes + z_bytes;
     hipError_t he = hipMalloc((void **)&h->mem, h->mem_bytes);
     if (he != hipSuccess) {
         h->mem = nullptr;
@@ -325,8 +323,7 @@ extern "C" ep_status ep_head_create(const ep_head_config *cfg, const void *ln_g,
     h->g = (float *)m; m += v_bytes;
     h->beta = (float *)m; m += v_bytes;
     h->rows = (float *)m; m += rows_bytes;
-    h->z = m; m += z_bytes;
-    h->part = h->part_floats ? (float *)m : nullptr;
+    h->z = m;
     try {
         std::vector<float> v;
         if ((he = hipMemcpy(h->w, w_head, (size_t)NC * D * psz, hipMemcpyHostToDevice)) != hipSuccess)
@@ -365,7 +362,7 @@ extern "C" ep_status ep_head_forward(ep_head_t *h, const void *x, int32_t B, voi
     if (h->bf16) {
         EP_HIP(ep_bf16_layernorm(h->rows, h->g, h->beta, c.ln_eps, (uint16_t *)h->z, B, D, s));
         EP_HIP(ep_bf16_gemm_skinny((const uint16_t *)h->z, (const uint16_t *)h->w, h->b, nullptr, logits, B, NC, D,
-                                   EPI_BIAS_F32, h->part, h->part_floats, s));
+                                   EPI_BIAS_F32, s));
     } else {
         EP_HIP(ep_f32_layernorm(h->rows, h->g, h->beta, c.ln_eps, (float *)h->z, B, D, s));
         EP_HIP(ep_f32_gemm((const float *)h->z, (const float *)h->w, h->b, nullptr, (float *)logits, B, NC, D, EPI_BIAS, s));

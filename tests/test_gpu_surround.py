@@ -56,7 +56,8 @@ def test_embedding_matches_checker(size, patch, channels, d, bf16):
     emb.destroy(); head.destroy()
 
 
-@pytest.mark.parametrize("d,T,nc,bf16", [(192, 65, 16, False), (192, 65, 16, True), (1280, 257, 1000, True), (768, 197, 1000, True)])
+@pytest.mark.parametrize("d,T,nc,bf16", [(192, 65, 16, False), (192, 65, 16, True), (1280, 257, 1000, True), (768, 197, 1000, True),
+                                         (2048, 17, 1000, True)])
 def test_head_matches_checker(d, T, nc, bf16):
     import torch
     sh = synth.custom_shape(f"head{d}", 1, d, max(1, d // 64), 4 * d, T)
