@@ -8,8 +8,8 @@
 // accumulation on the matrix cores (v_mfma_f32_32x32x16_bf16).
 //
 // This file holds the one-tile-per-workgroup kernel used for problems too small
-// for the persistent kernel (ep_gemm_bf16_persist.hip), the table of tile
-// configurations behind ep_bf16_gemm_config, and the dispatcher ep_bf16_gemm.
+// for the persistent kernel (ep_gemm_bf16_persist.hip) and the dispatcher
+// ep_bf16_gemm.
 //
 // Tiling.  A workgroup owns a BM x BN tile of C and walks K in steps of BK (64
 // or 32).  Each K step's A and W panels live in LDS as rows of 16-byte chunks;
@@ -263,47 +263,18 @@ hipError_t launch_epi(const uint16_t *A, const uint16_t *W, const float *bias, c
 
 }  // namespace
 
-int ep_bf16_gemm_num_configs() { return 18; }
-
-hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, const float *bias,
-                               const float *resid, void *C, int64_t M, int N, int K, int epi,
-                               hipStream_t s)
+// The small-problem kernel: 128 x 128 tiles, K step 64, two stages, 4 waves, two workgroups per
+// compute unit.
+hipError_t ep_bf16_gemm_small(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
+                              void *C, int64_t M, int N, int K, int epi, hipStream_t s)
 {
     if (M <= 0 || N <= 0) return hipSuccess;
     if (K <= 0 || K % 64 != 0 || N % 4 != 0) return hipErrorInvalidValue;
-    // byte offsets inside the kernels are 32-bit
+    // byte offsets inside the kernel are 32-bit
     if (M * (int64_t)K * 2 >= 0x7FFFFFF0ll || (int64_t)N * K * 2 >= 0x7FFFFFF0ll || M * (int64_t)N >= (1ll << 31))
         return hipErrorInvalidValue;
     if (epi == EPI_BIAS_RESID && !resid) return hipErrorInvalidValue;
-    switch (cfg) {
-    case 0: return launch_epi<256, 256, 64, 2, 2, 4>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 1: return launch_epi<256, 256, 64, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 2: return launch_epi<256, 128, 64, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 3: return launch_epi<128, 128, 64, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 4: return launch_epi<256, 256, 32, 4, 2, 4>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 5: return launch_epi<256, 256, 32, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 6: return launch_epi<256, 128, 64, 3, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 7: return launch_epi<256, 128, 32, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 8: return launch_epi<128, 128, 64, 3, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 9: return launch_epi<256, 128, 32, 3, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 10: return launch_epi<128, 256, 32, 3, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 11: return launch_epi<128, 128, 32, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 12: return launch_epi<256, 128, 32, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
-    case 13: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 256, false, s);
-    case 14: return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M, N, K, epi, 320, false, s);
-    case 15: return ep_bf16_gemm_skinny(A, W, bias, resid, C, M, N, K, epi, s);
-    case 16:   // the tile walk over the whole 256-row tiles, the remaining rows in the same launch
-        return ep_bf16_gemm_persistent(A, W, bias, resid, C, M, M / 256 * 256, N, K, epi, 0, true, s);
-    case 17: { // the same split as two launches
-        const int64_t mm = M / 256 * 256;
-        hipError_t e = ep_bf16_gemm_persistent(A, W, bias, resid, C, M, mm, N, K, epi, 0, false, s);
-        if (e != hipSuccess || mm == M) return e;
-        const size_t csz = epi == EPI_BIAS_RESID ? 4 : 2;
-        return ep_bf16_gemm_skinny(A + mm * K, W, bias, resid ? resid + mm * N : nullptr,
-                                   (char *)C + (size_t)mm * N * csz, M - mm, N, K, epi, s);
-    }
-    }
-    return hipErrorInvalidValue;
+    return launch_epi<128, 128, 64, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
 }
 
 namespace {
@@ -362,7 +333,7 @@ hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias,
 {
     const GemmPlan p = plan_gemm(M, N, K);
     hipError_t e = p.bn ? ep_bf16_gemm_persistent(A, W, bias, resid, C, M, p.m_main, N, K, epi, p.bn, p.fused, s)
-                        : ep_bf16_gemm_config(3, A, W, bias, resid, C, M, N, K, epi, s);
+                        : ep_bf16_gemm_small(A, W, bias, resid, C, M, N, K, epi, s);
     if (e != hipSuccess) return e;
     if (after_main && (e = hipEventRecord(after_main, s)) != hipSuccess) return e;
     if (p.m_main == M || p.fused) return hipSuccess;

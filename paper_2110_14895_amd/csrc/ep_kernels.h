@@ -42,11 +42,9 @@ bool ep_bf16_attention_supported(int T, int d_head);
 // deterministic fill used by the profiler (values in [-1, 1])
 hipError_t ep_fill_pattern(float *x, int64_t n, hipStream_t s);
 
-// tile-configuration sweep hooks of the bf16 GEMM (0 <= cfg < ep_bf16_gemm_num_configs())
-int ep_bf16_gemm_num_configs();
-hipError_t ep_bf16_gemm_config(int cfg, const uint16_t *A, const uint16_t *W, const float *bias,
-                               const float *resid, void *C, int64_t M, int N, int K, int epi,
-                               hipStream_t s);
+// one 128 x 128 tile per workgroup: problems too small for the persistent kernel
+hipError_t ep_bf16_gemm_small(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
+                              void *C, int64_t M, int N, int K, int epi, hipStream_t s);
 
 // persistent kernel for large problems (ep_gemm_bf16_persist.hip): 256 x BN tiles, BN = tile_bn
 // (256 or 320; 0 = pick the one with fewer weighted rounds).  The tile walk covers rows
