@@ -147,11 +147,11 @@ typedef enum {
     EP_K_FC2 = 6,  /* second dense layer + residual */
     EP_K_COUNT = 7,
     /*
-     * A dense layer may take two launches: one over the rows of whole 256-row
-     * tiles (which, for short K, also takes the row remainder in its last phase)
-     * and, for long K, a small one over the row remainder.  These ids time the
-     * first launch alone (bf16 path only; it is the whole layer when there is no
-     * second launch); ep_stage_gemm_main_rows gives the rows it covers.
+     * The launch of a dense layer alone (bf16 path only), without the event
+     * bracket's share of the neighbouring kernels' gaps that ids 2, 3, 5, 6 see;
+     * ep_stage_gemm_main_rows gives the rows it covers (all rows of the layer: a
+     * dense layer is one launch, the rows past the last whole 256-row tile are
+     * computed in its last phase).
      */
     EP_K_QKV_MAIN = 7,
     EP_K_PROJ_MAIN = 8,

@@ -279,11 +279,10 @@ hipError_t ep_bf16_gemm_small(const uint16_t *A, const uint16_t *W, const float 
 
 namespace {
 
-// How ep_bf16_gemm cuts the problem: rows [0, m_main) go to the persistent kernel with
-// tile width bn (bn = 0: the one-tile-per-workgroup kernel takes all rows).  Rows [m_main, M)
-// are short-M work: with `fused` the persistent launch computes them after its tile walk,
-// otherwise the short-M kernel does.
-struct GemmPlan { int64_t m_main; int bn; bool fused; };
+// How ep_bf16_gemm cuts the problem: the persistent kernel with tile width bn walks the tiles
+// of rows [0, m_main) and computes rows [m_main, M) in its tail phase (bn = 0: the
+// one-tile-per-workgroup kernel takes all rows).  Either way a dense layer is one launch.
+struct GemmPlan { int64_t m_main; int bn; };
 
 // Cost of the tail phase in the units of ep_bf16_gemm_persistent_cost (a round of 256 x bn tiles
 // costs bn): a round of 64 x 32 tiles over the compute units takes about a tenth of a round of
@@ -305,7 +304,7 @@ GemmPlan plan_gemm(int64_t M, int N, int K)
         int bn_all = 0;
         const int64_t cost_all = ep_bf16_gemm_persistent_cost(M, N, &bn_all);
         const int64_t tiles_all = ((M + 255) / 256) * ((N + bn_all - 1) / bn_all);
-        GemmPlan best = {M, tiles_all >= 192 ? bn_all : 0, false};
+        GemmPlan best = {M, tiles_all >= 192 ? bn_all : 0};
         int64_t best_cost = tiles_all >= 192 ? cost_all : INT64_MAX;
         for (int64_t m_main = M / 256 * 256; m_main > 0 && M - m_main < 512; m_main -= 256) {
             const int64_t tail = M - m_main;
@@ -313,31 +312,28 @@ GemmPlan plan_gemm(int64_t M, int N, int K)
             int bn_main = 0;
             const int64_t cost = ep_bf16_gemm_persistent_cost(m_main, N, &bn_main) + tail_cost(tail, N);
             const int64_t tiles_main = (m_main / 256) * ((N + bn_main - 1) / bn_main);
-            if (tiles_main >= 192 && cost < best_cost) { best = {m_main, bn_main, true}; best_cost = cost; }
+            if (tiles_main >= 192 && cost < best_cost) { best = {m_main, bn_main}; best_cost = cost; }
         }
         if (best.bn) return best;
     }
-    return {M, 0, false};
+    return {M, 0};
 }
 
 }  // namespace
 
 int64_t ep_bf16_gemm_main_rows(int64_t M, int N, int K)
 {
-    const GemmPlan p = plan_gemm(M, N, K);
-    return p.fused ? M : p.m_main;
+    (void)N; (void)K;
+    return M;                                        // a dense layer is one launch over all its rows
 }
 
 hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
                         void *C, int64_t M, int N, int K, int epi, hipEvent_t after_main, hipStream_t s)
 {
     const GemmPlan p = plan_gemm(M, N, K);
-    hipError_t e = p.bn ? ep_bf16_gemm_persistent(A, W, bias, resid, C, M, p.m_main, N, K, epi, p.bn, p.fused, s)
+    hipError_t e = p.bn ? ep_bf16_gemm_persistent(A, W, bias, resid, C, M, p.m_main, N, K, epi, p.bn, true, s)
                         : ep_bf16_gemm_small(A, W, bias, resid, C, M, N, K, epi, s);
     if (e != hipSuccess) return e;
-    if (after_main && (e = hipEventRecord(after_main, s)) != hipSuccess) return e;
-    if (p.m_main == M || p.fused) return hipSuccess;
-    const size_t csz = epi == EPI_BIAS_RESID ? 4 : 2;
-    return ep_bf16_gemm_skinny(A + p.m_main * K, W, bias, resid ? resid + p.m_main * N : nullptr,
-                               (char *)C + (size_t)p.m_main * N * csz, M - p.m_main, N, K, epi, s);
+    if (after_main) e = hipEventRecord(after_main, s);
+    return e;
 }

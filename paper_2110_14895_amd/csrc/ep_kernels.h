@@ -28,8 +28,8 @@ hipError_t ep_bf16_layernorm(const float *x, const float *g, const float *b, flo
 hipError_t ep_bf16_to_f32(const uint16_t *in, float *out, int64_t n, hipStream_t s);
 hipError_t ep_f32_to_bf16(const float *in, uint16_t *out, int64_t n, hipStream_t s);
 // A bf16 [M, K], W bf16 [N, K]; out bf16 (EPI_BIAS, EPI_BIAS_GELU) or fp32 (EPI_BIAS_RESID).
-// after_main: if non-null, recorded on s right after the first launch (the rows
-// ep_bf16_gemm_main_rows reports), for timing that launch alone.
+// after_main: if non-null, recorded on s right after the launch (it covers the rows
+// ep_bf16_gemm_main_rows reports: all of them).
 hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias,
                         const float *resid, void *C, int64_t M, int N, int K, int epi,
                         hipEvent_t after_main, hipStream_t s);
