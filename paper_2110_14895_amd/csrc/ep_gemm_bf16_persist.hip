@@ -14,18 +14,25 @@
 //     L2 -> LDS path moves ~1.6x faster than half lines).  A step's A and W
 //     panels go from global memory straight into LDS with buffer_load ... lds
 //     (no register staging), two stages; the loads a wave issues per step are
-//     slipped one by one between MFMAs, dealt over three 16-wide slices: the
-//     first right after the barrier that retires the stage they overwrite, the
-//     rest in the first two slices of the following step (a burst of all of
-//     them holds every wave at the door of the memory pipeline at once); the
+//     slipped one by one between MFMAs, dealt over three quarters of a step:
+//     the first right after the barrier that retires the stage they overwrite,
+//     the rest in the first two quarters of the following step (a burst of all
+//     of them holds every wave at the door of the memory pipeline at once); the
 //     last of them still has half a step to land.
 //   - LDS rows are 8 chunks of 16 bytes; chunk c of row r sits at slot
-//     c ^ f(r), f(r) = (r & 7) ^ ((r >> 3) & 1): the 16-byte fragment reads of 32
-//     consecutive rows are conflict-free on the 64-bank LDS.
-//   - Fragments are double-buffered in registers and every LDS read of the
-//     next slice is issued between two MFMAs of the current one, so a wave has
-//     no phase without matrix work except the one barrier per step.
-// Epilogue: 32 x 32 accumulator blocks (+bias, GELU) are transposed through the
+//     c ^ f(r), f(r) = (r & 7) ^ ((r >> 3) & 1): the 16-byte fragment reads of 16
+//     consecutive rows are conflict-free on the 64-bank LDS (with the K chunks
+//     dealt to the quarters of a wave in the order 0, 2, 1, 3).
+//   - The matrix instruction is v_mfma_f32_16x16x32_bf16: at the power limit
+//     the chip runs the same flops about 15 % faster in this form than as
+//     32 x 32 x 16.  A 32-wide slice of the wave tile is multiplied in four
+//     units of (half the activation fragments) x (half the weight fragments),
+//     ordered so that consecutive units share one of their halves; the
+//     registers of a retired half take the fragments needed two units later,
+//     every LDS read is issued between two MFMAs at least a unit ahead of its
+//     use, and a wave has no phase without matrix work except the one barrier
+//     per step.
+// Epilogue: 32 x 32 blocks of accumulators (+bias, GELU) are transposed through the
 // LDS stage the tile's last step has just retired (4 KB per wave), so that
 // global stores and residual loads are whole row segments; the refill of that
 // stage for the next tile is issued right after.  The tile's bias values wait
@@ -54,12 +61,11 @@
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int BM = 256, BK = 64, STAGES = 2;
 constexpr int NW = 8;                                // waves
 constexpr int CPR = BK / 8;                          // 8 chunks of 16 B per LDS row
-constexpr int NSL = BK / 16;                         // 16-wide K slices per step
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 4;
 
@@ -67,18 +73,18 @@ constexpr int GROUP_M = 4;
 template <int BN_, int WM_, int WN_>
 struct Tile {
     static constexpr int BN = BN_, WM = WM_, WN = WN_;
-    static constexpr int MI = BM / WM / 32, NI = BN / WN / 32;        // 32x32 accumulators per wave
+    static constexpr int MI = BM / WM / 32, NI = BN / WN / 32;        // 32 x 32 blocks of the wave tile (epilogue)
+    static constexpr int MI16 = 2 * MI, NI16 = 2 * NI;                // 16 x 16 accumulators per wave
     static constexpr int A_STAGE = BM * CPR, W_STAGE = BN * CPR;      // uint4 per stage and operand
     static constexpr int STAGE_U4 = A_STAGE + W_STAGE;
     static constexpr int LDA = BM / 8 / NW, LDW = BN / 8 / NW;        // loads per wave per step (8 rows each)
     static constexpr size_t SMEM = (size_t)(STAGES * STAGE_U4 + BN / 4) * sizeof(uint4);   // stages + the tile's bias
     static_assert(WM * WN == NW && BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BN % (8 * NW) == 0, "tile shape");
-    // a step's loads are dealt over three slices (a burst of all of them holds every wave at the
-    // memory pipeline's door at once): [0, P0) in the last slice of the step before the previous one's
-    // end, [P0, P1) in slice 0 and [P1, LDA+LDW) in slice 1 of the step in between
+    // a step's loads are dealt over three quarters of a step (a burst of all of them holds every wave at
+    // the memory pipeline's door at once): [0, P0) in the last quarter of the step before the previous
+    // one's end, [P0, P1) in the first and [P1, LDA+LDW) in the second quarter of the step in between
     static constexpr int P0 = 3, P1 = 6;
-    static_assert(P0 <= MI * NI && P1 - P0 <= MI * NI && LDA + LDW - P1 <= MI * NI && P1 < LDA + LDW, "one load per MFMA");
-    static_assert(MI + NI <= MI * NI, "one fragment read per MFMA");
+    static_assert(P1 < LDA + LDW, "three groups of loads");
     static_assert(STAGE_U4 >= NW * 256, "a stage must hold 4 KB of epilogue staging per wave");
 };
 typedef Tile<256, 2, 4> Tile256;                     // wave tile 128 x 64
@@ -100,7 +106,6 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
     constexpr int BN = T::BN, WN = T::WN, MI = T::MI, NI = T::NI;
     constexpr int A_STAGE = T::A_STAGE, STAGE_U4 = T::STAGE_U4, LDA = T::LDA, LDW = T::LDW;
     constexpr int NLD = LDA + LDW, P0 = T::P0, P1 = T::P1;
-    constexpr int NMFMA = MI * NI;
 
     extern __shared__ uint4 lds[];                   // [STAGES][A panel | W panel]
     typedef __attribute__((address_space(3))) void *lds_ptr;
@@ -108,7 +113,6 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: wave-derived addressing stays scalar
     const int wm0 = (wave / WN) * (MI * 32), wn0 = (wave % WN) * (NI * 32);
-    const int l31 = lane & 31, g = lane >> 5;
 
     // ---- this workgroup's tile list: tile j has logical id j*G + (w%8)*(G/8) + w/8
     const int G = gridDim.x;                         // multiple of 8
@@ -178,30 +182,51 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
         }
     };
 
-    // ---- fragment reads: offsets in uint4 inside a stage
-    const int fsw = swz(l31);
-    const int a_row = (wm0 + l31) * CPR, w_row = A_STAGE + (wn0 + l31) * CPR;
-    bf16x8 fa[2][MI], fw[2][NI];
-    // j = 0 .. NI-1: W fragment j; j = NI .. NI+MI-1: A fragment j-NI (the order the MFMAs first need them)
-    auto read_frag = [&](const uint4 *base, int slice, int buf, int j) {
-        const int col = (slice * 2 + g) ^ fsw;
-        if (j < NI) fw[buf][j] = __builtin_bit_cast(bf16x8, base[w_row + j * 32 * CPR + col]);
-        else fa[buf][j - NI] = __builtin_bit_cast(bf16x8, base[a_row + (j - NI) * 32 * CPR + col]);
+    // ---- fragments and accumulators (v_mfma_f32_16x16x32_bf16).  A fragment is 16 panel rows by 32 of K
+    // (lane l: row l % 16, one 8-element K chunk per quarter l / 16 of the wave); accumulator (wi, ai) <->
+    // columns wi*16 + 4*(l/16) + i, row ai*16 + l%16.  A 32-wide slice of the wave tile is multiplied in four
+    // units (P half, H half): P is the side with fewer fragments, both sides are split in halves, and the
+    // units run (a,0) (b,0) (b,1) (a,1) with a, b swapping from slice to slice, so that from one unit to the
+    // next only one half changes and the registers of the half just retired take the fragments needed two
+    // units later: one slice's worth of fragment registers in all, every read a unit or more ahead.
+    constexpr int MI16 = T::MI16, NI16 = T::NI16;
+    constexpr bool P_ACT = MI16 <= NI16;
+    constexpr int PH = (P_ACT ? MI16 : NI16) / 2, HH = (P_ACT ? NI16 : MI16) / 2;
+    constexpr int UM = PH * HH;                      // MFMAs per unit
+    static_assert(PH + 2 * HH <= 2 * UM && 2 * HH <= UM && (UM + 1) / 2 >= P0 && (UM + 1) / 2 >= P1 - P0 &&
+                      (UM + 1) / 2 >= NLD - P1,
+                  "reads and loads fit between the MFMAs of their units");
+    const int l15 = lane & 15, g4 = lane >> 4;
+    const int fsw = swz(l15);
+    // quarter g4 of the wave multiplies K chunk kc4 of a slice (any assignment works as long as both
+    // operands use it); 0, 2, 1, 3 keeps the 16-byte reads of the four quarters off each other's banks
+    const int kc4 = ((g4 & 1) << 1) | (g4 >> 1);
+    const int p_row = P_ACT ? (wm0 + l15) * CPR : A_STAGE + (wn0 + l15) * CPR;
+    const int h_row = P_ACT ? A_STAGE + (wn0 + l15) * CPR : (wm0 + l15) * CPR;
+    bf16x8 fp[2][PH], fh[2][HH];
+    f32x4 acc[NI16][MI16];
+    auto read_p = [&](const uint4 *base, int slice, int half, int j) {
+        fp[half][j] = __builtin_bit_cast(bf16x8, base[p_row + (half * PH + j) * 16 * CPR + ((slice * 4 + kc4) ^ fsw)]);
     };
-
-    f32x16 acc[NI][MI];
+    auto read_h = [&](const uint4 *base, int slice, int half, int j) {
+        fh[half][j] = __builtin_bit_cast(bf16x8, base[h_row + (half * HH + j) * 16 * CPR + ((slice * 4 + kc4) ^ fsw)]);
+    };
     auto zero_acc = [&]() {
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+        for (int wi = 0; wi < NI16; ++wi)
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
+            for (int ai = 0; ai < MI16; ++ai)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[ni][mi][i] = 0.f;
+                for (int i = 0; i < 4; ++i) acc[wi][ai][i] = 0.f;
     };
-    // MFMA q of a slice: ni fastest
-    auto mfma_one = [&](int buf, int q) {
-        const int ni = q % NI, mi = q / NI;
-        acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][ni], fa[buf][mi], acc[ni][mi], 0, 0, 0);
+    // MFMA q of unit (hp, hh): H fragment fastest
+    auto mfma_one = [&](int hp, int hh, int q) {
+        const int jp = q / HH, jh = q % HH;
+        const int ip = hp * PH + jp, ih = hh * HH + jh;
+        if (P_ACT)
+            acc[ih][ip] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fh[hh][jh], fp[hp][jp], acc[ih][ip], 0, 0, 0);
+        else
+            acc[ip][ih] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fp[hp][jp], fh[hh][jh], acc[ip][ih], 0, 0, 0);
     };
 
     // The BN bias values of a tile sit in LDS behind the stages, brought there with 4-byte
@@ -219,13 +244,19 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                                                      0, 0);
         }
     };
-    auto bias4 = [&](int col) {                      // col: column inside the tile, a multiple of 8
-        return *reinterpret_cast<const float4 *>(bias_lds + col + 4 * g);
+    auto bias4 = [&](int col, int g4) {              // col: column inside the tile, a multiple of 16; g4 = lane / 16
+        return *reinterpret_cast<const float4 *>(bias_lds + col + 4 * g4);
     };
 
     // ---- epilogue of the tile at (m0, n0); `stage` has just been retired and is free LDS.
-    // acc[ni][mi][i] <-> column ni*32 + 8*(i/4) + 4*g + (i%4), row mi*32 + (lane&31).
+    // It goes by 32 x 32 blocks: four accumulators (wj, aj) each.
     auto epilogue = [&](int m0, int n0, int stage) {
+        // the lane-dependent addressing of the epilogue is derived afresh for every tile from a lane index
+        // the compiler cannot see through: otherwise it computes all of it ahead of the K loop, where the
+        // values do not fit in registers next to the accumulators and come back from scratch memory
+        int le = lane;
+        asm volatile("" : "+v"(le));
+        const int l15 = le & 15, g4 = le >> 4, lane = le;
         uint4 *stg = lds + stage * STAGE_U4 + wave * 256;           // 4 KB
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
@@ -235,16 +266,19 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                 if (EPI == EPI_BIAS_RESID) {
                     // block [32 m][32 n] fp32: rows of 128 B = 8 chunks of 4 floats
                     float *C = reinterpret_cast<float *>(Cout);
-                    float4 bq[4];                    // the block's 32 bias values in one go: one wait, not four
+                    float4 bq[2];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) bq[q] = bias4(wn0 + ni * 32 + q * 8);
+                    for (int wj = 0; wj < 2; ++wj) bq[wj] = bias4(wn0 + ni * 32 + wj * 16, g4);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float4 bb = bq[q];
-                        const float4 v = make_float4(acc[ni][mi][q * 4 + 0] + bb.x, acc[ni][mi][q * 4 + 1] + bb.y,
-                                                     acc[ni][mi][q * 4 + 2] + bb.z, acc[ni][mi][q * 4 + 3] + bb.w);
-                        *reinterpret_cast<float4 *>(&stg[l31 * 8 + ((q * 2 + g) ^ (l31 & 7))]) = v;
-                    }
+                    for (int aj = 0; aj < 2; ++aj)
+#pragma unroll
+                        for (int wj = 0; wj < 2; ++wj) {
+                            const f32x4 c = acc[ni * 2 + wj][mi * 2 + aj];
+                            const float4 bb = bq[wj];
+                            const int r = aj * 16 + l15;
+                            *reinterpret_cast<float4 *>(&stg[r * 8 + ((wj * 4 + g4) ^ (r & 7))]) =
+                                make_float4(c[0] + bb.x, c[1] + bb.y, c[2] + bb.z, c[3] + bb.w);
+                        }
                     const int rrow = lane >> 3, rc = lane & 7;      // read-back: 8 rows x 8 chunks per pass
                     float4 v[4], x[4];
 #pragma unroll
@@ -266,22 +300,25 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                     // c ^ ((r >> 2) & 3): four rows span the 64 banks, so the 8-byte writes of 32 rows meet two to
                     // a bank (the best a 64-byte row stride allows) and the 16-byte reads of 4 rows not at all
                     uint16_t *C = reinterpret_cast<uint16_t *>(Cout);
-                    float4 bq[4];
+                    float4 bq[2];
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) bq[q] = bias4(wn0 + ni * 32 + q * 8);
+                    for (int wj = 0; wj < 2; ++wj) bq[wj] = bias4(wn0 + ni * 32 + wj * 16, g4);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const float4 bb = bq[q];
-                        float v0 = acc[ni][mi][q * 4 + 0] + bb.x, v1 = acc[ni][mi][q * 4 + 1] + bb.y;
-                        float v2 = acc[ni][mi][q * 4 + 2] + bb.z, v3 = acc[ni][mi][q * 4 + 3] + bb.w;
-                        if (EPI == EPI_BIAS_GELU) {
-                            v0 = gelu_erf(v0); v1 = gelu_erf(v1); v2 = gelu_erf(v2); v3 = gelu_erf(v3);
+                    for (int aj = 0; aj < 2; ++aj)
+#pragma unroll
+                        for (int wj = 0; wj < 2; ++wj) {
+                            const f32x4 c = acc[ni * 2 + wj][mi * 2 + aj];
+                            const float4 bb = bq[wj];
+                            float v0 = c[0] + bb.x, v1 = c[1] + bb.y, v2 = c[2] + bb.z, v3 = c[3] + bb.w;
+                            if (EPI == EPI_BIAS_GELU) {
+                                v0 = gelu_erf(v0); v1 = gelu_erf(v1); v2 = gelu_erf(v2); v3 = gelu_erf(v3);
+                            }
+                            uint2 o;
+                            o.x = pack_bf16x2(v0, v1);
+                            o.y = pack_bf16x2(v2, v3);
+                            const int r = aj * 16 + l15;
+                            reinterpret_cast<uint2 *>(&stg[r * 4 + ((wj * 2 + (g4 >> 1)) ^ ((r >> 2) & 3))])[g4 & 1] = o;
                         }
-                        uint2 o;
-                        o.x = pack_bf16x2(v0, v1);
-                        o.y = pack_bf16x2(v2, v3);
-                        reinterpret_cast<uint2 *>(&stg[l31 * 4 + (q ^ ((l31 >> 2) & 3))])[g] = o;
-                    }
                     const int rrow = lane >> 2, rc = lane & 3;      // read-back: 16 rows x 4 chunks per pass
 #pragma unroll
                     for (int p = 0; p < 2; ++p) {
@@ -304,7 +341,9 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
     EP_WAIT_VMCNT0();
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int j = 0; j < NI + MI; ++j) read_frag(lds, 0, 0, j);
+    for (int j = 0; j < PH; ++j) read_p(lds, 0, 0, j);
+#pragma unroll
+    for (int j = 0; j < HH; ++j) read_h(lds, 0, 0, j);
 #pragma unroll
     for (int q = 0; q < P0; ++q) issue_one(q);
 
@@ -313,33 +352,46 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
         const uint4 *cur = lds + (it & 1) * STAGE_U4;
         const uint4 *nxt = lds + ((it + 1) & 1) * STAGE_U4;
         const bool tile_end = c_kt == KT - 1;
-        // slices 0 .. NSL-2: multiply slice sl (buffer sl&1) while reading slice sl+1; slices 0 and 1
-        // also issue the rest of the next step's loads into the other stage
+        // two 32-wide slices of four units; the stage swap sits before the last two units of the step
 #pragma unroll
-        for (int sl = 0; sl < NSL - 1; ++sl) {
+        for (int s = 0; s < 2; ++s) {
 #pragma unroll
-            for (int q = 0; q < NMFMA; ++q) {
-                mfma_one(sl & 1, q);
-                if (sl == 0 && q == 0) EP_SCHED_FENCE();    // the step's first MFMA waits for old reads only
-                if (q < NI + MI) read_frag(cur, sl + 1, (sl + 1) & 1, q);
-                if (sl == 0 && P0 + q < P1) issue_one(P0 + q);
-                if (sl == 1 && P1 + q < NLD) issue_one(P1 + q);
-                EP_SCHED_FENCE();
+            for (int u = 0; u < 4; ++u) {
+                const int pa = s, pb = s ^ 1;                   // P half of units 0, 3 and of units 1, 2
+                const int hp = (u == 0 || u == 3) ? pa : pb, hh = u >> 1;
+                const bool post = s == 1 && u >= 2;
+                if (s == 1 && u == 2) {
+                    advance_load();
+                    // all my reads of this stage are done; the next step has landed; swap
+                    EP_WAIT_LGKMCNT0();
+                    EP_WAIT_VMCNT0();
+                    __builtin_amdgcn_s_barrier();
+                }
+                const uint4 *src = post ? nxt : cur;            // units 2, 3 read the slice after this one
+                const int rs = u < 2 ? s : (s ^ 1);
+#pragma unroll
+                for (int q = 0; q < UM; ++q) {
+                    mfma_one(hp, hh, q);
+                    if (s == 0 && u == 0 && q == 0) EP_SCHED_FENCE();   // the step's first MFMA waits for old reads only
+                    // fragment reads: the P half of unit 1 first, the H half of units 2, 3 at every other
+                    // MFMA of units 0, 1; the next slice's H half at every other MFMA of unit 2 and its P half
+                    // at the start of unit 3 (the loads below take the MFMA slots in between)
+                    if (u == 0 && q < PH) read_p(src, rs, pb, q);
+                    if (u < 2) {
+                        const int t = u * UM + q - PH;          // slots after the P reads
+                        if (t >= 0 && (t & 1) && (t >> 1) < HH) read_h(src, rs, 1, t >> 1);
+                    }
+                    if (u == 2 && (q & 1) && (q >> 1) < HH) read_h(src, rs, 0, q >> 1);
+                    if (u == 3 && q < PH) read_p(src, rs, pb, q);
+                    if ((q & 1) == 0) {                         // the loads keep their spacing of two MFMA slots
+                        const int k = q >> 1;
+                        if (s == 0 && u == 0 && P0 + k < P1) issue_one(P0 + k);
+                        if (s == 0 && u == 2 && P1 + k < NLD) issue_one(P1 + k);
+                        if (post && u == 2 && k < P0 && !tile_end) issue_one(k);
+                    }
+                    EP_SCHED_FENCE();
+                }
             }
-        }
-        advance_load();
-        // all my reads of this stage are done; the next step has landed; swap
-        EP_WAIT_LGKMCNT0();
-        EP_WAIT_VMCNT0();
-        __builtin_amdgcn_s_barrier();
-        // last slice: read the next step's first fragments and start refilling the retired stage
-        // (at the end of a tile the stage first serves the epilogue and the refill starts after it)
-#pragma unroll
-        for (int q = 0; q < NMFMA; ++q) {
-            mfma_one((NSL - 1) & 1, q);
-            if (q < NI + MI) read_frag(nxt, 0, 0, q);
-            if (q < P0 && !tile_end) issue_one(q);
-            EP_SCHED_FENCE();
         }
         if (tile_end) {
             int m0, n0;
