@@ -219,9 +219,10 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 #pragma unroll
                 for (int i = 0; i < 4; ++i) acc[wi][ai][i] = 0.f;
     };
-    // MFMA q of unit (hp, hh): H fragment fastest
+    // MFMA q of unit (hp, hh): the P fragments back and forth under each H fragment, so that consecutive
+    // MFMAs share one operand (a little faster than changing both)
     auto mfma_one = [&](int hp, int hh, int q) {
-        const int jp = q / HH, jh = q % HH;
+        const int jh = q / PH, jp = (jh & 1) ? PH - 1 - q % PH : q % PH;
         const int ip = hp * PH + jp, ih = hh * HH + jh;
         if (P_ACT)
             acc[ih][ip] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fh[hh][jh], fp[hp][jp], acc[ih][ip], 0, 0, 0);
