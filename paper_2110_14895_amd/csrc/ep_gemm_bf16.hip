@@ -5,7 +5,7 @@
 //   C[M, N] = A[M, K] . W[N, K]^T + bias[N]   (+ erf GELU | + fp32 residual)
 //
 // A: bf16 activations, W: bf16 weights [out, in], both K-contiguous, fp32
-// accumulation on the matrix cores (v_mfma_f32_32x32x16_bf16).
+// accumulation on the matrix cores (v_mfma_f32_16x16x32_bf16).
 //
 // This file holds the one-tile-per-workgroup kernel used for problems too small
 // for the persistent kernel (ep_gemm_bf16_persist.hip) and the dispatcher
@@ -17,8 +17,9 @@
 // fragment reads bank-conflict free without padding.  The panels go from global
 // memory straight into LDS (buffer_load ... lds), STAGES - 1 steps ahead of the
 // MFMAs, with explicit s_waitcnt counts and one bare s_barrier per step.
-// Waves are laid out WM x WN; each wave keeps (BN/WN/32) x (BM/WM/32)
-// accumulators of 32x32.
+// Waves are laid out WM x WN; each wave keeps (BN/WN/16) x (BM/WM/16)
+// accumulators of 16x16 (the 16x16x32 form of the instruction draws less power
+// per flop than 32x32x16, and power is what limits the clock in these loops).
 //
 // Operand roles are swapped with respect to C: the MFMA "A" operand is the W
 // fragment (rows = output columns n) and the "B" operand is the activation
@@ -45,7 +46,7 @@
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int NUM_XCD = 8;
 constexpr int GROUP_M = 4;
@@ -82,11 +83,12 @@ __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * 
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int NW = WM * WN;                       // waves
     constexpr int WTM = BM / WM, WTN = BN / WN;       // wave tile
-    constexpr int MI = WTM / 32, NI = WTN / 32;       // 32x32 accumulators per wave
+    constexpr int MI = WTM / 16, NI = WTN / 16;       // 16x16 accumulators per wave
     constexpr int CPR = BK_ / 8;                      // 16-byte chunks per LDS row
     constexpr int RPI = 64 / CPR;                     // rows covered by one wave-wide 16-byte load
     constexpr int A_LD = BM / RPI / NW, W_LD = BN / RPI / NW;   // load instructions per wave per tile
     static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "panel must split evenly over waves");
+    static_assert(BK_ % 32 == 0 && WTM % 16 == 0 && WTN % 16 == 0, "16 x 16 x 32 fragments");
     constexpr int A_STAGE = BM * CPR, W_STAGE = BN * CPR;       // uint4 per stage
 
     extern __shared__ uint4 lds[];                    // [STAGES][A_STAGE] then [STAGES][W_STAGE]
@@ -109,7 +111,7 @@ __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * 
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm0 = (wave / WN) * WTM, wn0 = (wave % WN) * WTN;
-    const int l31 = lane & 31, g = lane >> 5;
+    const int l15 = lane & 15, g4 = lane >> 4;
 
     // ---- global -> LDS, asynchronous (buffer_load ... lds): instruction i of this wave
     // fills rows (i*NW + wave)*RPI .. +RPI-1 of the panel; lane l lands at row l/CPR,
@@ -149,21 +151,25 @@ __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * 
                                                      live ? w_off[i] : 0x7FFFFFF0, koff, 0, 0);
     };
 
-    f32x16 acc[NI][MI];
+    f32x4 acc[NI][MI];
 #pragma unroll
     for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[ni][mi][i] = 0.f;
+            for (int i = 0; i < 4; ++i) acc[ni][mi][i] = 0.f;
 
-    // fragment read offsets (uint4 units) inside a stage; the swizzle depends on the lane only
-    const int fsw = swz<BK_>(l31);
-    int a_rd[BK_ / 16], w_rd[BK_ / 16];
+    // fragment read offsets (uint4 units) inside a stage; the swizzle depends on the lane only.  A
+    // fragment is 16 rows by 32 of K: lane l reads row l % 16 and one 8-element K chunk per quarter
+    // l / 16 of the wave, the chunks dealt 0, 2, 1, 3 (both operands alike), which keeps the 16-byte reads
+    // of the four quarters off each other's banks.
+    const int fsw = swz<BK_>(l15);
+    const int kc4 = ((g4 & 1) << 1) | (g4 >> 1);
+    int a_rd[BK_ / 32], w_rd[BK_ / 32];
 #pragma unroll
-    for (int kk = 0; kk < BK_ / 16; ++kk) {
-        a_rd[kk] = (wm0 + l31) * CPR + ((kk * 2 + g) ^ fsw);
-        w_rd[kk] = (wn0 + l31) * CPR + ((kk * 2 + g) ^ fsw);
+    for (int kk = 0; kk < BK_ / 32; ++kk) {
+        a_rd[kk] = (wm0 + l15) * CPR + ((kk * 4 + kc4) ^ fsw);
+        w_rd[kk] = (wn0 + l15) * CPR + ((kk * 4 + kc4) ^ fsw);
     }
 
 #pragma unroll
@@ -177,37 +183,36 @@ __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * 
         const uint4 *Ab = As + (kt % STAGES) * A_STAGE;
         const uint4 *Wb = Ws + (kt % STAGES) * W_STAGE;
 #pragma unroll
-        for (int kk = 0; kk < BK_ / 16; ++kk) {
+        for (int kk = 0; kk < BK_ / 32; ++kk) {
             bf16x8 wf[NI], af[MI];
 #pragma unroll
-            for (int ni = 0; ni < NI; ++ni) wf[ni] = __builtin_bit_cast(bf16x8, Wb[w_rd[kk] + ni * 32 * CPR]);
+            for (int ni = 0; ni < NI; ++ni) wf[ni] = __builtin_bit_cast(bf16x8, Wb[w_rd[kk] + ni * 16 * CPR]);
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) af[mi] = __builtin_bit_cast(bf16x8, Ab[a_rd[kk] + mi * 32 * CPR]);
+            for (int mi = 0; mi < MI; ++mi) af[mi] = __builtin_bit_cast(bf16x8, Ab[a_rd[kk] + mi * 16 * CPR]);
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
-                    acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[ni], af[mi], acc[ni][mi], 0, 0, 0);
+                    acc[ni][mi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[ni], af[mi], acc[ni][mi], 0, 0, 0);
         }
     }
     EP_WAIT_VMCNT(0);                          // drain the (empty) tail loads before LDS goes away
 
-    // ---- epilogue.  acc[ni][mi][i]: n = ni*32 + 8*(i/4) + 4*g + (i%4), m = mi*32 + (lane&31)
+    // ---- epilogue.  acc[ni][mi][i]: n = ni*16 + 4*(lane/16) + i, m = mi*16 + lane%16
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
-        const int m = m0 + wm0 + mi * 32 + l31;
+        const int m = m0 + wm0 + mi * 16 + l15;
         if (m >= M) continue;
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn0 + ni * 32 + q * 8 + g * 4;
+            {
+                const int n = n0 + wn0 + ni * 16 + g4 * 4;
                 if (n >= N) continue;
                 const float4 bb = *reinterpret_cast<const float4 *>(bias + n);
-                float v0 = acc[ni][mi][q * 4 + 0] + bb.x;
-                float v1 = acc[ni][mi][q * 4 + 1] + bb.y;
-                float v2 = acc[ni][mi][q * 4 + 2] + bb.z;
-                float v3 = acc[ni][mi][q * 4 + 3] + bb.w;
+                float v0 = acc[ni][mi][0] + bb.x;
+                float v1 = acc[ni][mi][1] + bb.y;
+                float v2 = acc[ni][mi][2] + bb.z;
+                float v3 = acc[ni][mi][3] + bb.w;
                 const size_t off = (size_t)m * N + n;
                 if (EPI == EPI_BIAS_RESID) {
                     const float4 r = *reinterpret_cast<const float4 *>(resid + off);
