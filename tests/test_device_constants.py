@@ -13,16 +13,19 @@ def test_device_gelu_polynomial_against_erf():
     hdr = open(os.path.join(os.path.dirname(__file__), "..", "paper_2110_14895_amd", "csrc", "ep_device.h")).read()
     body = re.search(r"#define EP_GELU_LOG2Q_COEFFS(.*?)\}", hdr, re.S).group(1)
     c = [np.float32(x.rstrip("f")) for x in re.findall(r"-?\d+\.\d+(?:e-?\d+)?f", body)]
-    assert len(c) == 7
+    assert len(c) == 5
     u = np.concatenate([np.linspace(-12, 12, 480001), [0.0, -0.0, 1e-30, -1e-30, 50.0, -50.0]]).astype(np.float32)
     a = np.minimum(np.abs(u), np.float32(6.0))
-    p = c[6] * a + c[5]
-    for k in (4, 3, 2, 1, 0):
+    p = c[4] * a + c[3]
+    for k in (2, 1, 0):
         p = (p * a + c[k]).astype(np.float32)
     got = (np.maximum(u, np.float32(0)) - np.exp2(p).astype(np.float32) * a).astype(np.float32)
     ref = np.array([0.5 * x * (1.0 + math.erf(x / math.sqrt(2.0))) for x in u.astype(np.float64)])
     err = np.abs(got.astype(np.float64) - ref)
-    # 1.5e-7 for the fit and its fp32 Horner evaluation, one fp32 rounding of the result on top
-    assert np.all(err <= 1.5e-7 + 1.2e-7 * np.abs(ref)), (err - 1.2e-7 * np.abs(ref)).max()
-    small = np.abs(u) <= 1.0
-    assert err[small].max() <= 1.5e-7
+    # the output format is bf16 (relative steps of 2^-8): the fit stays an order of magnitude
+    # below it, 6.5e-6 absolute everywhere and 3.5e-4 relative on the positive side
+    assert err.max() <= 6.5e-6, err.max()
+    pos = u > 0
+    assert np.all(err[pos] <= 3.5e-4 * ref[pos] + 1e-37), (err[pos] / np.maximum(ref[pos], 1e-300)).max()
+    # far from the origin the correction term vanishes: identity on the right, zero on the left
+    assert np.all(got[u >= 9] == u[u >= 9]) and np.all(np.abs(got[u <= -9]) < 1e-8)
