@@ -33,9 +33,10 @@
 //     use, and a wave has no phase without matrix work except the one barrier
 //     per step.
 // Epilogue: 32 x 32 blocks of accumulators (+bias, GELU) are transposed through the
-// LDS stage the tile's last step has just retired (4 KB per wave), so that
-// global stores and residual loads are whole row segments; the refill of that
-// stage for the next tile is issued right after.  The tile's bias values wait
+// W part of the LDS stage the tile's last step has just retired (4 KB per wave),
+// so that global stores and residual loads are whole row segments; the refill of
+// the stage's A part for the next tile is already under way meanwhile (issued
+// before the epilogue, like after any other step), the rest follows it.  The tile's bias values wait
 // in LDS (loaded there during the K loop).
 //
 // Operand roles are swapped (MFMA A = W fragment, B = activation fragment) so
@@ -85,7 +86,8 @@ struct Tile {
     // one's end, [P0, P1) in the first and [P1, LDA+LDW) in the second quarter of the step in between
     static constexpr int P0 = 3, P1 = 6;
     static_assert(P1 < LDA + LDW, "three groups of loads");
-    static_assert(STAGE_U4 >= NW * 256, "a stage must hold 4 KB of epilogue staging per wave");
+    // the first group refills the A part of a retired stage while the epilogue stages through its W part
+    static_assert(P0 <= LDA && W_STAGE >= NW * 256, "first loads: A panel only; 4 KB of staging per wave in the W part");
 };
 typedef Tile<256, 2, 4> Tile256;                     // wave tile 128 x 64
 typedef Tile<320, 4, 2> Tile320;                     // wave tile 64 x 160
@@ -196,20 +198,32 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
     static_assert(PH + 2 * HH <= 2 * UM && 2 * HH <= UM && (UM + 1) / 2 >= P0 && (UM + 1) / 2 >= P1 - P0 &&
                       (UM + 1) / 2 >= NLD - P1,
                   "reads and loads fit between the MFMAs of their units");
-    const int l15 = lane & 15, g4 = lane >> 4;
-    const int fsw = swz(l15);
     // quarter g4 of the wave multiplies K chunk kc4 of a slice (any assignment works as long as both
-    // operands use it); 0, 2, 1, 3 keeps the 16-byte reads of the four quarters off each other's banks
-    const int kc4 = ((g4 & 1) << 1) | (g4 >> 1);
-    const int p_row = P_ACT ? (wm0 + l15) * CPR : A_STAGE + (wn0 + l15) * CPR;
-    const int h_row = P_ACT ? A_STAGE + (wn0 + l15) * CPR : (wm0 + l15) * CPR;
+    // operands use it); 0, 2, 1, 3 keeps the 16-byte reads of the four quarters off each other's banks.
+    // The offsets are derived again after every epilogue (from a lane index the compiler cannot see
+    // through), so that they do not occupy registers while a tile is stored.
+    int p_off[2], h_off[2];                          // per 32-wide slice
+    auto derive_read_offsets = [&]() {
+        int le = lane;
+        asm volatile("" : "+v"(le));
+        const int l15 = le & 15, g4 = le >> 4;
+        const int fsw = swz(l15), kc4 = ((g4 & 1) << 1) | (g4 >> 1);
+        const int p_row = P_ACT ? (wm0 + l15) * CPR : A_STAGE + (wn0 + l15) * CPR;
+        const int h_row = P_ACT ? A_STAGE + (wn0 + l15) * CPR : (wm0 + l15) * CPR;
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) {
+            p_off[sl] = p_row + ((sl * 4 + kc4) ^ fsw);
+            h_off[sl] = h_row + ((sl * 4 + kc4) ^ fsw);
+        }
+    };
+    derive_read_offsets();
     bf16x8 fp[2][PH], fh[2][HH];
     f32x4 acc[NI16][MI16];
     auto read_p = [&](const uint4 *base, int slice, int half, int j) {
-        fp[half][j] = __builtin_bit_cast(bf16x8, base[p_row + (half * PH + j) * 16 * CPR + ((slice * 4 + kc4) ^ fsw)]);
+        fp[half][j] = __builtin_bit_cast(bf16x8, base[p_off[slice] + (half * PH + j) * 16 * CPR]);
     };
     auto read_h = [&](const uint4 *base, int slice, int half, int j) {
-        fh[half][j] = __builtin_bit_cast(bf16x8, base[h_row + (half * HH + j) * 16 * CPR + ((slice * 4 + kc4) ^ fsw)]);
+        fh[half][j] = __builtin_bit_cast(bf16x8, base[h_off[slice] + (half * HH + j) * 16 * CPR]);
     };
     auto zero_acc = [&]() {
 #pragma unroll
@@ -258,7 +272,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
         int le = lane;
         asm volatile("" : "+v"(le));
         const int l15 = le & 15, g4 = le >> 4, lane = le;
-        uint4 *stg = lds + stage * STAGE_U4 + wave * 256;           // 4 KB
+        uint4 *stg = lds + stage * STAGE_U4 + A_STAGE + wave * 256; // 4 KB of the W panel's part
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) {
 #pragma unroll
@@ -388,7 +402,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                         const int k = q >> 1;
                         if (s == 0 && u == 0 && P0 + k < P1) issue_one(P0 + k);
                         if (s == 0 && u == 2 && P1 + k < NLD) issue_one(P1 + k);
-                        if (post && u == 2 && k < P0 && !tile_end) issue_one(k);
+                        if (post && u == 2 && k < P0) issue_one(k);
                     }
                     EP_SCHED_FENCE();
                 }
@@ -404,8 +418,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
             EP_WAIT_LGKMCNT0();
             __builtin_amdgcn_s_barrier();           // every wave is done with the staging area and the bias
             issue_bias(c_seq);
-#pragma unroll
-            for (int q = 0; q < P0; ++q) issue_one(q);
+            derive_read_offsets();
         } else {
             ++c_kt;
         }
