@@ -36,8 +36,8 @@
 // W part of the LDS stage the tile's last step has just retired (4 KB per wave),
 // so that global stores and residual loads are whole row segments; the refill of
 // the stage's A part for the next tile is already under way meanwhile (issued
-// before the epilogue, like after any other step), the rest follows it.  The tile's bias values wait
-// in LDS (loaded there during the K loop).
+// before the epilogue, like after any other step), the rest follows it.  The
+// tile's bias values wait in LDS (loaded there during the K loop).
 //
 // Operand roles are swapped (MFMA A = W fragment, B = activation fragment) so
 // that a lane owns 4 consecutive output columns of one row.
@@ -91,7 +91,6 @@ struct Tile {
 };
 typedef Tile<256, 2, 4> Tile256;                     // wave tile 128 x 64
 typedef Tile<320, 4, 2> Tile320;                     // wave tile 64 x 160
-
 
 #define EP_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0 | (0x0 << 14) | (0x7 << 4) | (0xF << 8))
 #define EP_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8))
