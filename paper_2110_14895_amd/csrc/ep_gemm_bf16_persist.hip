@@ -81,13 +81,21 @@ struct Tile {
     static constexpr int LDA = BM / 8 / NW, LDW = BN / 8 / NW;        // loads per wave per step (8 rows each)
     static constexpr size_t SMEM = (size_t)(STAGES * STAGE_U4 + BN / 4) * sizeof(uint4);   // stages + the tile's bias
     static_assert(WM * WN == NW && BM % (WM * 32) == 0 && BN % (WN * 32) == 0 && BN % (8 * NW) == 0, "tile shape");
-    // a step's loads are dealt over three quarters of a step (a burst of all of them holds every wave at
-    // the memory pipeline's door at once): [0, P0) in the last quarter of the step before the previous
-    // one's end, [P0, P1) in the first and [P1, LDA+LDW) in the second quarter of the step in between
-    static constexpr int P0 = 3, P1 = 6;
-    static_assert(P1 < LDA + LDW, "three groups of loads");
-    // the first group refills the A part of a retired stage while the epilogue stages through its W part
-    static_assert(P0 <= LDA && W_STAGE >= NW * 256, "first loads: A panel only; 4 KB of staging per wave in the W part");
+    // A step's loads are dealt over three groups (a burst of all of them holds every wave at the memory
+    // pipeline's door at once): [0, P0) right after the barrier that retires the stage they fill, [P0, P1)
+    // in the first unit of the next step and [P1, LDA+LDW) in its third unit - or, in the `early` variant
+    // of the kernel, one load more in the first group and the last group in the second unit.  The early
+    // variant serves launches of a single round of tiles, where every operand line is a first touch for
+    // its L2 and takes longer to arrive (FC2 at 16448 rows: -5.8 us); where a workgroup walks several
+    // tiles and finds the W panels of its earlier ones in L2, it costs time (FC1 at 65792 rows: +4.5 %).
+    template <bool EARLY>
+    struct Deal {
+        static constexpr int P0 = EARLY ? 4 : 3, P1 = P0 + 3, LAST_UNIT = EARLY ? 1 : 2;
+        static_assert(P1 < LDA + LDW, "three groups of loads");
+        // the first group refills the A part of a retired stage while the epilogue stages through its W part
+        static_assert(P0 <= LDA, "first loads: A panel only");
+    };
+    static_assert(W_STAGE >= NW * 256, "4 KB of epilogue staging per wave in the W part of a stage");
 };
 typedef Tile<256, 2, 4> Tile256;                     // wave tile 128 x 64
 typedef Tile<320, 4, 2> Tile320;                     // wave tile 64 x 160
@@ -98,7 +106,7 @@ typedef Tile<320, 4, 2> Tile320;                     // wave tile 64 x 160
 
 __device__ inline int swz(int row) { return (row & 7) ^ ((row >> 3) & 1); }
 
-template <class T, int EPI>
+template <class T, int EPI, bool EARLY>
 __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const float *__restrict__ bias,
     const float *resid, void *Cout, int M, int m_rows, int N, int K, int tiles_m, int tiles_n, int tail_rows, int tail_tm)
@@ -106,7 +114,8 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int BN = T::BN, WN = T::WN, MI = T::MI, NI = T::NI;
     constexpr int A_STAGE = T::A_STAGE, STAGE_U4 = T::STAGE_U4, LDA = T::LDA, LDW = T::LDW;
-    constexpr int NLD = LDA + LDW, P0 = T::P0, P1 = T::P1;
+    typedef typename T::template Deal<EARLY> Deal;
+    constexpr int NLD = LDA + LDW, P0 = Deal::P0, P1 = Deal::P1, LAST_UNIT = Deal::LAST_UNIT;
 
     extern __shared__ uint4 lds[];                   // [STAGES][A panel | W panel]
     typedef __attribute__((address_space(3))) void *lds_ptr;
@@ -400,7 +409,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
                     if ((q & 1) == 0) {                         // the loads keep their spacing of two MFMA slots
                         const int k = q >> 1;
                         if (s == 0 && u == 0 && P0 + k < P1) issue_one(P0 + k);
-                        if (s == 0 && u == 2 && P1 + k < NLD) issue_one(P1 + k);
+                        if (s == 0 && u == LAST_UNIT && P1 + k < NLD) issue_one(P1 + k);
                         if (post && u == 2 && k < P0) issue_one(k);
                     }
                     EP_SCHED_FENCE();
@@ -461,18 +470,9 @@ int pick_tail_rows(int tail_rows, int N, int wgs)
     return best;
 }
 
-template <class T, int EPI>
-hipError_t launch_persistent(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
-                             void *C, int M, int m_rows, int N, int K, int tail_rows, hipStream_t s)
+// one resident workgroup per compute unit, a multiple of the number of XCDs
+hipError_t init_grid()
 {
-    auto kern = gemm_bf16_persistent_kernel<T, EPI>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::SMEM);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     if (!g_grid) {
         hipError_t e;
         int dev = 0, cus = 0;
@@ -480,6 +480,21 @@ hipError_t launch_persistent(const uint16_t *A, const uint16_t *W, const float *
         if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
         g_grid = cus / NUM_XCD * NUM_XCD;
         if (g_grid < NUM_XCD) g_grid = NUM_XCD;
+    }
+    return hipSuccess;
+}
+
+template <class T, int EPI, bool EARLY>
+hipError_t launch_persistent(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
+                             void *C, int M, int m_rows, int N, int K, int tail_rows, hipStream_t s)
+{
+    auto kern = gemm_bf16_persistent_kernel<T, EPI, EARLY>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::SMEM);
+        if (e != hipSuccess) return e;
+        attr_set = true;
     }
     const int tiles_m = (m_rows + BM - 1) / BM, tiles_n = (N + T::BN - 1) / T::BN;
     hipLaunchKernelGGL(kern, dim3(g_grid), dim3(NW * 64), T::SMEM, s, A, W, bias, resid, C, M, m_rows, N, K,
@@ -491,10 +506,17 @@ template <class T>
 hipError_t launch_tile(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid, void *C,
                        int M, int m_rows, int N, int K, int epi, int tail_rows, hipStream_t s)
 {
-    switch (epi) {
-    case EPI_BIAS: return launch_persistent<T, EPI_BIAS>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
-    case EPI_BIAS_GELU: return launch_persistent<T, EPI_BIAS_GELU>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
-    case EPI_BIAS_RESID: return launch_persistent<T, EPI_BIAS_RESID>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
+    const hipError_t e = init_grid();
+    if (e != hipSuccess) return e;
+    // a single round of tiles: the variant that sends a step's loads out earlier
+    const bool early = (int64_t)((m_rows + BM - 1) / BM) * ((N + T::BN - 1) / T::BN) <= g_grid;
+    switch (epi * 2 + (early ? 1 : 0)) {
+    case EPI_BIAS * 2: return launch_persistent<T, EPI_BIAS, false>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
+    case EPI_BIAS * 2 + 1: return launch_persistent<T, EPI_BIAS, true>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
+    case EPI_BIAS_GELU * 2: return launch_persistent<T, EPI_BIAS_GELU, false>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
+    case EPI_BIAS_GELU * 2 + 1: return launch_persistent<T, EPI_BIAS_GELU, true>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
+    case EPI_BIAS_RESID * 2: return launch_persistent<T, EPI_BIAS_RESID, false>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
+    case EPI_BIAS_RESID * 2 + 1: return launch_persistent<T, EPI_BIAS_RESID, true>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
     }
     return hipErrorInvalidValue;
 }
