@@ -20,10 +20,10 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16
 # HBM bytes per launch of the dominant kernel at the headline workload, from two rocprofv3 --pmc
 # runs of this script (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the
-# input conversion kernel, whose traffic is known: 308.1 MB fetched + 180.2 MB written
+# input conversion kernel, whose traffic is known: 308.2 MB fetched + 179.9 MB written
 # (profiles/vit_huge_b64_fc1_hbm_traffic.md).  Valid for the kernel as profiled; set to None when
 # the kernel changes until the counters are taken again.
-FC1_MAIN_TRAFFIC_BYTES = 308.1e6 + 180.2e6
+FC1_MAIN_TRAFFIC_BYTES = 308.2e6 + 179.9e6
 
 
 def main() -> int:
