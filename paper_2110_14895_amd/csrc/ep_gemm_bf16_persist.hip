@@ -254,7 +254,7 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 
     // The BN bias values of a tile sit in LDS behind the stages, brought there with 4-byte
     // global -> LDS loads when the tile before it is stored (columns past N read as zeros), so the
-    // epilogue gets its lane's four values with one LDS read and no select between the halves of
+    // epilogue gets its lane's four values with one LDS read and no select between the quarters of
     // the wave; the loads ride on the K loop's own waits.
     float *bias_lds = reinterpret_cast<float *>(lds + STAGES * STAGE_U4);
     const __amdgpu_buffer_rsrc_t b_rs =
