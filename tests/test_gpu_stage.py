@@ -244,6 +244,27 @@ def test_vit_huge_row_remainder_shapes(B):
     st.destroy()
 
 
+def test_vit_huge_batch_256_rows_past_the_tile_walk():
+    # 256 * 257 rows = 257 tiles of 256 rows: a 257th tile row would cost the layers of width 1280 a fifth
+    # round of tiles, so their tile walk stops a tile row early and the last phase of the launch takes
+    # the 256 rows left (all of them rows of the last image); the wider layers walk all 257 tile rows
+    sh = synth.SHAPES["vit_huge"]
+    B = 256
+    layers = layers_of(sh, 1, bf16=True, affine=True)
+    st = H.make_stage(sh, layers, 0, 1, B, bf16=True)
+    x = synth.activations(sh, B, bf16=True)
+    got = H.run_stage(st, x)
+    assert np.isfinite(got).all()
+    for i in (0, 127, B - 1):
+        ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x[i:i + 1])[0]
+        e = H.rel_err(got[i], ref)
+        print(f"ViT-Huge 1 layer B={B} image {i}: err {e:.3e}")
+        assert e <= H.TOL_BF16
+    rms = np.sqrt((got.astype(np.float64) ** 2).mean(axis=(1, 2)))
+    assert np.all(np.abs(rms / rms[0] - 1) < 0.2)
+    st.destroy()
+
+
 def test_vit_huge_all_layers_batch_64_sampled_images():
     # the benchmark configuration: 32 layers, B=64, T=257; the checker recomputes two images
     sh = synth.SHAPES["vit_huge"]
