@@ -300,24 +300,29 @@ int64_t tail_cost(int64_t tail_rows, int N)
 
 GemmPlan plan_gemm(int64_t M, int N, int K)
 {
-    // At least one full round of 256-row tiles over the compute units: the persistent kernel.
-    // The tile walk covers all rows, or stops one or two tile rows short of M and leaves the rest
-    // (at most 511 rows) to the tail phase of the same launch when that saves a round of tiles:
-    // a round of the narrow tail tiles is an order of magnitude cheaper.  Otherwise 128x128 tiles,
-    // two workgroups per compute unit, which quantise better on small micro-batches.
+    // The persistent kernel (256-row tiles, one workgroup per compute unit) when its tiles fill most of
+    // the chip, or already from about a hundred tiles on when the alternative, 128x128 tiles at two
+    // workgroups per compute unit, would need a second round (a launch of the persistent kernel takes
+    // about as long for 128 tiles as for 256, and that is less than two rounds of the small tiles:
+    // 130 against 153 us for the second MLP layer at 8224 rows).  The tile walk covers all rows, or stops
+    // one or two tile rows short of M and leaves the rest (at most 511 rows) to the tail phase of the
+    // same launch when that saves a round of tiles: a round of the narrow tail tiles is an order of
+    // magnitude cheaper.  Otherwise the 128x128 tiles, which quantise better on small micro-batches.
     if (ep_bf16_gemm_persistent_supported(M, N, K)) {
+        const int64_t small_tiles = ((M + 127) / 128) * ((N + 127) / 128);
+        const int64_t min_tiles = small_tiles <= 2 * (int64_t)ep_bf16_gemm_persistent_workgroups() ? 192 : 96;
         int bn_all = 0;
         const int64_t cost_all = ep_bf16_gemm_persistent_cost(M, N, &bn_all);
         const int64_t tiles_all = ((M + 255) / 256) * ((N + bn_all - 1) / bn_all);
-        GemmPlan best = {M, tiles_all >= 192 ? bn_all : 0};
-        int64_t best_cost = tiles_all >= 192 ? cost_all : INT64_MAX;
+        GemmPlan best = {M, tiles_all >= min_tiles ? bn_all : 0};
+        int64_t best_cost = tiles_all >= min_tiles ? cost_all : INT64_MAX;
         for (int64_t m_main = M / 256 * 256; m_main > 0 && M - m_main < 512; m_main -= 256) {
             const int64_t tail = M - m_main;
             if (tail == 0 || !ep_bf16_gemm_skinny_supported(tail, N, K)) continue;
             int bn_main = 0;
             const int64_t cost = ep_bf16_gemm_persistent_cost(m_main, N, &bn_main) + tail_cost(tail, N);
             const int64_t tiles_main = (m_main / 256) * ((N + bn_main - 1) / bn_main);
-            if (tiles_main >= 192 && cost < best_cost) { best = {m_main, bn_main}; best_cost = cost; }
+            if (tiles_main >= min_tiles && cost < best_cost) { best = {m_main, bn_main}; best_cost = cost; }
         }
         if (best.bn) return best;
     }

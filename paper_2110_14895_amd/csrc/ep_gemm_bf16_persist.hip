@@ -537,9 +537,11 @@ bool ep_bf16_gemm_persistent_supported(int64_t M, int N, int K)
            M * (int64_t)K * 2 < 0x7FFFFFF0ll && (int64_t)N * K * 2 < 0x7FFFFFF0ll && M * (int64_t)N < (1ll << 31);
 }
 
+int ep_bf16_gemm_persistent_workgroups() { return g_grid ? g_grid : 256; }
+
 int64_t ep_bf16_gemm_persistent_cost(int64_t rows, int N, int *tile_bn)
 {
-    const int cus = g_grid ? g_grid : 256;
+    const int cus = ep_bf16_gemm_persistent_workgroups();
     const int64_t c256 = tile_cost(rows, N, 256, cus), c320 = tile_cost(rows, N, 320, cus);
     if (tile_bn) *tile_bn = c320 <= c256 ? 320 : 256;      // a tie goes to the wider tile (fewer bytes loaded per flop)
     return c320 <= c256 ? c320 : c256;
