@@ -20,7 +20,9 @@
  *     the last error of the calling thread is ep_last_error().
  *   - "host" / "device" on a pointer says where the memory lives.  The library
  *     never takes ownership of a caller buffer.
- *   - A stage handle is not thread-safe; distinct handles are independent.
+ *   - A stage handle is not thread-safe; distinct handles are independent and
+ *     may be driven from distinct host threads (the library's one-time launch
+ *     set-up is kept per device and is safe against concurrent first calls).
  *   - One GPU: the device current at ep_stage_create is the stage's device.
  */
 #ifndef EDGEPIPE_H
@@ -180,6 +182,24 @@ ep_status ep_stage_trace_end(ep_stage_t *stage, int32_t *launches, double *secon
  * micro-batch B: what a roofline figure for that launch has to count.
  */
 ep_status ep_stage_gemm_main_rows(const ep_stage_t *stage, int32_t B, int32_t kernel, int64_t *rows);
+
+/*
+ * Measurement hook: the rate this device sustains on a loop of nothing but
+ * bf16 matrix instructions (no memory traffic), the yardstick a dense layer's
+ * achieved rate is read against next to the published peak (the dense layers
+ * are where a layer's time goes, section 5.1).  form 0: 16x16x32 (the form
+ * the dense layers use), form 1: 32x32x16.  random_operands 0: every operand
+ * value is 1.0; 1: random signs, mantissas and magnitudes in [0.5, 2) (the
+ * chip lowers its clock under the switching activity of real data).  One
+ * workgroup of 8 waves per compute unit runs 16 * iters instructions per wave,
+ * timed with events on `stream` (a hipStream_t) after a short warm-up launch.
+ * Outputs (HOST): *tflops; *shader_mhz (may be NULL) the shader clock the loop
+ * ran at, from the ratio of the shader cycle counter to the 100 MHz counter.
+ * Allocates and frees a small device buffer and synchronises `stream`.
+ * Errors: INVALID_ARG (form, iters outside [1, 2^24], null), OOM, HIP.
+ */
+ep_status ep_mfma_peak(int32_t form, int32_t random_operands, int32_t iters, void *stream,
+                       double *tflops, double *shader_mhz);
 
 /* Configuration, layer range and max_batch the stage was created with (HOST outputs,
  * each may be NULL). */

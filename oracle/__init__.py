@@ -9,4 +9,4 @@ imports nothing from the GPU library.
 """
 from .surround import embed_forward, head_forward, patches  # noqa: F401
 from .vit import (OracleConfig, attention, gelu, layer_forward, layernorm, linear,  # noqa: F401
-                  num_threads, stage_forward)
+                  num_threads, round_bf16, stage_forward)

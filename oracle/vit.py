@@ -61,6 +61,8 @@ def lib() -> C.CDLL:
         L.epo_layer_forward.argtypes = [C.POINTER(_Cfg), C.POINTER(_Layer), C.c_int32, _DP]
         L.epo_stage_forward.argtypes = [C.POINTER(_Cfg), C.c_int32, C.POINTER(_Layer), _FP,
                                         C.c_int32, _DP]
+        L.epo_round_bf16.argtypes = [C.c_double]
+        L.epo_round_bf16.restype = C.c_double
         for f in (L.epo_layer_forward, L.epo_stage_forward, L.epo_num_threads):
             f.restype = C.c_int
         _lib = L
@@ -85,6 +87,12 @@ def _dp(a: Optional[np.ndarray]):
 
 def num_threads() -> int:
     return int(lib().epo_num_threads())
+
+
+def round_bf16(v: float) -> float:
+    """The narrowing the diagnostic mode applies at the five operand points: float64 -> float32 ->
+    bf16, both steps round-to-nearest-even; infinities and NaN pass through."""
+    return float(lib().epo_round_bf16(float(v)))
 
 
 def layernorm(x, g, b, eps: float) -> np.ndarray:

@@ -55,8 +55,9 @@ typedef struct {
 } epo_layer;
 
 /* bf16 round-to-nearest-even of a double that is first narrowed to float32
- * (the GPU pipeline narrows from float32 accumulators). */
-static double round_bf16(double v)
+ * (the GPU pipeline narrows from float32 accumulators).  Exported so that the
+ * tests can pin it on its own: ties, double rounding, infinities, NaN. */
+double epo_round_bf16(double v)
 {
     float f = (float)v;
     uint32_t b;
@@ -71,7 +72,7 @@ static double round_bf16(double v)
 static void maybe_round(double *a, size_t n, int mode)
 {
     if (!mode) return;
-    for (size_t i = 0; i < n; ++i) a[i] = round_bf16(a[i]);
+    for (size_t i = 0; i < n; ++i) a[i] = epo_round_bf16(a[i]);
 }
 
 /* y[r, :] = (x[r, :] - mean) / sqrt(var + eps) * g + b, mean and biased
@@ -149,7 +150,7 @@ void epo_attention(const double *qkv, int32_t T, int32_t D, int32_t H, int round
             for (int32_t u = 0; u < T; ++u) s[u] /= z;
             if (probs) memcpy(probs + ((int64_t)h * T + t) * T, s, sizeof(double) * (size_t)T);
             if (round_mode)
-                for (int32_t u = 0; u < T; ++u) s[u] = round_bf16(s[u]);
+                for (int32_t u = 0; u < T; ++u) s[u] = epo_round_bf16(s[u]);
             for (int32_t e = 0; e < dh; ++e) {
                 double acc = 0.0;
                 for (int32_t u = 0; u < T; ++u)

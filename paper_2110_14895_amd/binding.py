@@ -91,6 +91,7 @@ def lib() -> C.CDLL:
         L.ep_stage_device_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_uint64)]
         L.ep_stage_destroy.argtypes = [C.c_void_p]
         L.ep_stage_destroy.restype = None
+        L.ep_mfma_peak.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, dp, dp]
         L.ep_partition.argtypes = [C.c_int32, C.c_int32, dp, dp, dp, dp, dp, dp, ip, ip, ip, ip]
         L.ep_partition_categories.argtypes = [C.c_int32, C.c_int32, dp, dp, dp, dp, dp, dp, ip, ip, ip, ip, ip]
         L.ep_status_string.argtypes = [C.c_int]
@@ -100,7 +101,7 @@ def lib() -> C.CDLL:
         for f in (L.ep_stage_create, L.ep_stage_forward, L.ep_stage_profile, L.ep_stage_trace_begin,
                   L.ep_stage_trace_end, L.ep_stage_gemm_main_rows, L.ep_stage_device_bytes, L.ep_partition,
                   L.ep_partition_categories, L.ep_stage_info, L.ep_pipeline_create, L.ep_pipeline_run,
-                  L.ep_embed_create, L.ep_embed_forward, L.ep_head_create, L.ep_head_forward):
+                  L.ep_embed_create, L.ep_embed_forward, L.ep_head_create, L.ep_head_forward, L.ep_mfma_peak):
             f.restype = C.c_int
         _lib = L
     return _lib
@@ -307,6 +308,14 @@ class Pipeline:
             self.destroy()
         except Exception:
             pass
+
+
+def mfma_peak(form: int, random_operands: bool, iters: int, stream=None) -> Tuple[float, float]:
+    """(TFLOP/s, shader MHz) of a loop of nothing but bf16 matrix instructions on the current device."""
+    tf, mhz = C.c_double(), C.c_double()
+    _check(lib().ep_mfma_peak(int(form), int(bool(random_operands)), int(iters), _stream(stream),
+                              C.byref(tf), C.byref(mhz)), "ep_mfma_peak")
+    return tf.value, mhz.value
 
 
 def partition_categories(t_comp, layer_mem, dev_mem, xfer_bytes, bw):

@@ -38,6 +38,7 @@
 // LDS buffers hold (T <= 32*NKT, NKT a multiple of 3).
 #include "ep_kernels.h"
 #include "ep_device.h"
+#include "ep_launch.h"
 #include <algorithm>
 
 namespace {
@@ -355,25 +356,16 @@ hipError_t launch_attn(const uint16_t *qkv, uint16_t *o, int B, int T, int D, in
 {
     using S = AttnShape<DH, NKT>;
     auto kern = attn_bf16_kernel<DH, NKT>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static EpSmemLimit smem_limit;
+    hipError_t e = smem_limit.ensure(reinterpret_cast<const void *>(kern), (int)S::smem);
+    if (e != hipSuccess) return e;
     const int nq = (T + 31) / 32;          // one wave per tile of 32 queries, <= NKT
     const int nw = nq + NPROD;             // ... and the producer waves
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
     // one persistent workgroup per compute unit (the LDS footprint allows no more); a multiple
     // of 8 keeps the XCD-aware pair ranges
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-    }
+    int n_cu = 0;
+    if ((e = ep_device_cu_count(&n_cu)) != hipSuccess) return e;
     const int n_pairs = B * H;
     int grid = n_pairs;
     if (n_pairs > n_cu) grid = n_cu;

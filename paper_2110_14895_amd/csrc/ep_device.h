@@ -29,7 +29,9 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
 __device__ inline float gelu_erf(float u)
 {
     constexpr float c[5] = EP_GELU_LOG2Q_COEFFS;
-    const float a = fminf(fabsf(u), 6.0f);
+    // the NaN-propagating minimum (one v_minimum3_f32, the cost of v_min_f32): a NaN pre-activation
+    // makes a, P(a) and the result NaN instead of vanishing in fminf / fmaxf
+    const float a = __builtin_elementwise_minimum(fabsf(u), 6.0f);
     float p = fmaf(c[4], a, c[3]);
     p = fmaf(p, a, c[2]);
     p = fmaf(p, a, c[1]);

@@ -42,6 +42,7 @@
 #include <cstdint>
 #include "ep_kernels.h"
 #include "ep_device.h"
+#include "ep_launch.h"
 
 namespace {
 
@@ -239,13 +240,9 @@ hipError_t launch_cfg(const uint16_t *A, const uint16_t *W, const float *bias, c
 {
     auto kern = gemm_bf16_kernel<BM, BN, BK_, STAGES, WM, WN, EPI>;
     constexpr size_t smem = (size_t)STAGES * (BM + BN) * (BK_ / 8) * sizeof(uint4);
-    static bool attr_set = false;   // benign race: the attribute call is idempotent
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static EpSmemLimit smem_limit;
+    const hipError_t e = smem_limit.ensure(reinterpret_cast<const void *>(kern), (int)smem);
+    if (e != hipSuccess) return e;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int total = tiles_m * tiles_n;
     const int grid = (total + NUM_XCD - 1) / NUM_XCD * NUM_XCD;

@@ -58,6 +58,7 @@
 #include "ep_kernels.h"
 #include "ep_device.h"
 #include "ep_gemm_bf16_skinny_tile.h"
+#include "ep_launch.h"
 
 namespace {
 
@@ -453,8 +454,6 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 #endif
 }
 
-int g_grid = 0;
-
 // Rows per tile (64, 32 or 16; all 32 columns wide) for the tail phase: the fewest rounds over the
 // workgroups, then the fewest bytes a workgroup pulls per tile (rows + 32 panel rows of K elements).
 int pick_tail_rows(int tail_rows, int N, int wgs)
@@ -470,32 +469,25 @@ int pick_tail_rows(int tail_rows, int N, int wgs)
     return best;
 }
 
-// one resident workgroup per compute unit, a multiple of the number of XCDs
-hipError_t init_grid()
+// one resident workgroup per compute unit of the current device, a multiple of the number of XCDs
+hipError_t resident_grid(int *grid)
 {
-    if (!g_grid) {
-        hipError_t e;
-        int dev = 0, cus = 0;
-        if ((e = hipGetDevice(&dev)) != hipSuccess) return e;
-        if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
-        g_grid = cus / NUM_XCD * NUM_XCD;
-        if (g_grid < NUM_XCD) g_grid = NUM_XCD;
-    }
+    int cus = 0;
+    const hipError_t e = ep_device_cu_count(&cus);
+    if (e != hipSuccess) return e;
+    *grid = cus / NUM_XCD * NUM_XCD;
+    if (*grid < NUM_XCD) *grid = NUM_XCD;
     return hipSuccess;
 }
 
 template <class T, int EPI, bool EARLY>
 hipError_t launch_persistent(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
-                             void *C, int M, int m_rows, int N, int K, int tail_rows, hipStream_t s)
+                             void *C, int M, int m_rows, int N, int K, int tail_rows, int g_grid, hipStream_t s)
 {
     auto kern = gemm_bf16_persistent_kernel<T, EPI, EARLY>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)T::SMEM);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static EpSmemLimit smem_limit;
+    const hipError_t e = smem_limit.ensure(reinterpret_cast<const void *>(kern), (int)T::SMEM);
+    if (e != hipSuccess) return e;
     const int tiles_m = (m_rows + BM - 1) / BM, tiles_n = (N + T::BN - 1) / T::BN;
     hipLaunchKernelGGL(kern, dim3(g_grid), dim3(NW * 64), T::SMEM, s, A, W, bias, resid, C, M, m_rows, N, K,
                        tiles_m, tiles_n, tail_rows, tail_rows ? pick_tail_rows(tail_rows, N, g_grid) : 0);
@@ -506,17 +498,18 @@ template <class T>
 hipError_t launch_tile(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid, void *C,
                        int M, int m_rows, int N, int K, int epi, int tail_rows, hipStream_t s)
 {
-    const hipError_t e = init_grid();
+    int g_grid = 0;
+    const hipError_t e = resident_grid(&g_grid);
     if (e != hipSuccess) return e;
     // a single round of tiles: the variant that sends a step's loads out earlier
     const bool early = (int64_t)((m_rows + BM - 1) / BM) * ((N + T::BN - 1) / T::BN) <= g_grid;
     switch (epi * 2 + (early ? 1 : 0)) {
-    case EPI_BIAS * 2: return launch_persistent<T, EPI_BIAS, false>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
-    case EPI_BIAS * 2 + 1: return launch_persistent<T, EPI_BIAS, true>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
-    case EPI_BIAS_GELU * 2: return launch_persistent<T, EPI_BIAS_GELU, false>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
-    case EPI_BIAS_GELU * 2 + 1: return launch_persistent<T, EPI_BIAS_GELU, true>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
-    case EPI_BIAS_RESID * 2: return launch_persistent<T, EPI_BIAS_RESID, false>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
-    case EPI_BIAS_RESID * 2 + 1: return launch_persistent<T, EPI_BIAS_RESID, true>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, s);
+    case EPI_BIAS * 2: return launch_persistent<T, EPI_BIAS, false>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, g_grid, s);
+    case EPI_BIAS * 2 + 1: return launch_persistent<T, EPI_BIAS, true>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, g_grid, s);
+    case EPI_BIAS_GELU * 2: return launch_persistent<T, EPI_BIAS_GELU, false>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, g_grid, s);
+    case EPI_BIAS_GELU * 2 + 1: return launch_persistent<T, EPI_BIAS_GELU, true>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, g_grid, s);
+    case EPI_BIAS_RESID * 2: return launch_persistent<T, EPI_BIAS_RESID, false>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, g_grid, s);
+    case EPI_BIAS_RESID * 2 + 1: return launch_persistent<T, EPI_BIAS_RESID, true>(A, W, bias, resid, C, M, m_rows, N, K, tail_rows, g_grid, s);
     }
     return hipErrorInvalidValue;
 }
@@ -537,7 +530,11 @@ bool ep_bf16_gemm_persistent_supported(int64_t M, int N, int K)
            M * (int64_t)K * 2 < 0x7FFFFFF0ll && (int64_t)N * K * 2 < 0x7FFFFFF0ll && M * (int64_t)N < (1ll << 31);
 }
 
-int ep_bf16_gemm_persistent_workgroups() { return g_grid ? g_grid : 256; }
+int ep_bf16_gemm_persistent_workgroups()
+{
+    int g = 0;
+    return resident_grid(&g) == hipSuccess ? g : 256;
+}
 
 int64_t ep_bf16_gemm_persistent_cost(int64_t rows, int N, int *tile_bn)
 {

@@ -19,6 +19,7 @@
 // stored.
 #include "ep_kernels.h"
 #include "ep_device.h"
+#include "ep_launch.h"
 #include "ep_gemm_bf16_skinny_tile.h"
 
 namespace {
@@ -43,13 +44,9 @@ hipError_t launch_skinny(const uint16_t *A, const uint16_t *W, const float *bias
                          int M, int N, int K, hipStream_t s)
 {
     auto kern = gemm_bf16_skinny_kernel<EPI>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static EpSmemLimit smem_limit;
+    const hipError_t e = smem_limit.ensure(reinterpret_cast<const void *>(kern), (int)SMEM);
+    if (e != hipSuccess) return e;
     const dim3 grid((N + TN - 1) / TN, (M + TM - 1) / TM);
     hipLaunchKernelGGL(kern, grid, dim3(NW * 64), SMEM, s, A, W, bias, resid, C, M, N, K);
     return hipGetLastError();

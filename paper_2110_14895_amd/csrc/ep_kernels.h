@@ -53,7 +53,7 @@ bool ep_bf16_gemm_persistent_supported(int64_t M, int N, int K);
 // rounds of tiles over the compute units times the tile width (lower is better); writes the
 // tile width it would pick
 int64_t ep_bf16_gemm_persistent_cost(int64_t rows, int N, int *tile_bn);
-// resident workgroups of a launch: one per compute unit (256 before the first launch has asked the device)
+// resident workgroups of a launch on the current device: one per compute unit (256 if the device cannot be asked)
 int ep_bf16_gemm_persistent_workgroups();
 hipError_t ep_bf16_gemm_persistent(const uint16_t *A, const uint16_t *W, const float *bias,
                                    const float *resid, void *C, int64_t M, int64_t m_rows, int N,

@@ -181,6 +181,20 @@ extern "C" ep_status ep_stage_create(const ep_vit_config *cfg, int32_t layer_beg
     const int64_t D = cfg->d_model, M = cfg->d_mlp, T = cfg->n_tokens;
     if ((int64_t)max_batch * T > (1ll << 24))
         return ep_fail(EP_ERR_UNSUPPORTED, "ep_stage_create: max_batch * n_tokens exceeds 2^24 rows");
+    {
+        // what the kernels of a forward over max_batch images index with 32 bits (or a 16-bit grid
+        // dimension): refuse here rather than in the middle of a forward
+        const int64_t R = (int64_t)max_batch * T, wide = 3 * D > M ? 3 * D : M, deep = D > M ? D : M;
+        bool fits;
+        if (cfg->param_dtype == EP_BF16)
+            fits = R * wide < (1ll << 31) && R * deep * 2 < 0x7FFFFFF0ll && wide * deep * 2 < 0x7FFFFFF0ll;
+        else
+            fits = (R + 63) / 64 <= 65535 && max_batch <= 65535 && cfg->n_heads <= 65535;
+        if (!fits)
+            return ep_fail(EP_ERR_UNSUPPORTED,
+                           "ep_stage_create: max_batch %d gives %lld rows, more than the dense layers of this "
+                           "width can index", max_batch, (long long)R);
+    }
     for (int l = 0; l < nl; ++l) {
         const ep_layer_weights &w = layers[l];
         if (!w.ln1_g || !w.ln1_b || !w.w_qkv || !w.b_qkv || !w.w_o || !w.b_o || !w.ln2_g || !w.ln2_b ||
@@ -310,6 +324,11 @@ extern "C" ep_status ep_stage_profile(ep_stage_t *st, int32_t B, int32_t iters, 
     if (!st || !per_layer_seconds) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_profile: null argument");
     if (B < 1 || B > st->max_batch || iters < 1)
         return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_profile: need 1 <= B <= max_batch and iters >= 1");
+    int dev = -1;
+    EP_HIP(hipGetDevice(&dev));
+    if (dev != st->device)
+        return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_profile: stage lives on device %d, current device is %d",
+                       st->device, dev);
     hipStream_t s = (hipStream_t)stream;
     const ep_vit_config &c = st->cfg;
     const int64_t n = (int64_t)B * c.n_tokens * c.d_model;

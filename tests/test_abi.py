@@ -77,6 +77,18 @@ def test_stage_create_rejects_null_parameter_pointers_and_bad_batch():
     assert lib.ep_stage_create(None, 0, 1, _null_layers(1), 1, C.byref(h)) == binding.EP_ERR_INVALID_ARG
 
 
+def test_stage_create_rejects_a_batch_the_dense_layers_cannot_index():
+    # 2000 images x 257 tokens x 5120 hidden columns is past the 32-bit element index of the dense
+    # layers: refused when the stage is built, not in the middle of a forward
+    lib = binding.lib()
+    h = C.c_void_p()
+    c = _cfg(n_layers=1, d_model=1280, n_heads=16, d_mlp=5120, n_tokens=257).c_struct()
+    assert lib.ep_stage_create(C.byref(c), 0, 1, _null_layers(1), 2000, C.byref(h)) == binding.EP_ERR_UNSUPPORTED
+    assert "rows" in binding.last_error() and not h.value
+    # the same width at a batch that fits gets as far as the parameter check
+    assert lib.ep_stage_create(C.byref(c), 0, 1, _null_layers(1), 256, C.byref(h)) == binding.EP_ERR_INVALID_ARG
+
+
 def test_forward_and_profile_reject_null_handle():
     lib = binding.lib()
     assert lib.ep_stage_forward(None, None, 1, None, None) == binding.EP_ERR_INVALID_ARG

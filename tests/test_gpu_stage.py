@@ -78,9 +78,20 @@ def test_bf16_small_shapes(T, D, Hh, M, B, part):
     ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x)
     ref_r = oracle.stage_forward(H.oracle_cfg(sh, round_mode=1), layers, x)
     e, er = H.rel_err(got, ref), H.rel_err(got, ref_r)
-    print(f"{part} T={T} D={D}: err {e:.3e}, vs operand-rounded reference {er:.3e}")
+    sd, sdr = H.err_std(got, ref), H.err_std(got, ref_r)
+    print(f"{part} T={T} D={D}: err {e:.3e} (std {sd:.3e}), vs operand-rounded reference {er:.3e} (std {sdr:.3e})")
     assert e <= H.TOL_BF16
-    assert er <= 1e-2          # agreement with the operand-rounded reference is much closer
+    # Against the operand-rounded reference.  With the attention branch switched off the two share
+    # their rounding points, and what is left are operands that land on the other side of a tie
+    # (mostly GELU outputs: the device's GELU is accurate to 3.5e-4 relative, a sixth of half a bf16
+    # step): a third of the unrounded error's spread or less (observed 0.25 .. 0.33; maximum
+    # 5.7e-4 .. 4.9e-3).  The attention kernel narrows the probabilities before it normalises them
+    # (the reference after), so with attention on the operand-rounded reference is no closer to the
+    # device than the unrounded one and only the graded bound is asserted.
+    if part == "mlp_only":
+        assert sdr <= 0.5 * sd and er <= 7.5e-3
+    else:
+        assert er <= H.TOL_BF16
 
 
 def test_bf16_zero_output_weights_is_exact_identity():
@@ -206,7 +217,7 @@ def test_vit_large_stage_of_six_layers_batch_sweep():
     st = H.make_stage(sh, layers, 0, 6, 64, bf16=True)
     # images are independent (section 2.1): image i gives the same result in any batch
     ref = {i: oracle.stage_forward(H.oracle_cfg(sh), layers, synth.activations(sh, 1, bf16=True, first_image=i))[0]
-           for i in (0, 31)}
+           for i in (0, 3, 9, 15, 22, 31, 40, 49, 58, 63)}
     for B in (1, 4, 16, 32, 64):
         x = synth.activations(sh, B, bf16=True)
         got = H.run_stage(st, x)
@@ -255,7 +266,7 @@ def test_vit_huge_batch_256_rows_past_the_tile_walk():
     x = synth.activations(sh, B, bf16=True)
     got = H.run_stage(st, x)
     assert np.isfinite(got).all()
-    for i in (0, 127, B - 1):
+    for i in (0, 37, 74, 111, 127, 148, 185, 222, B - 1):
         ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x[i:i + 1])[0]
         e = H.rel_err(got[i], ref)
         print(f"ViT-Huge 1 layer B={B} image {i}: err {e:.3e}")
@@ -266,24 +277,42 @@ def test_vit_huge_batch_256_rows_past_the_tile_walk():
 
 
 def test_vit_huge_all_layers_batch_64_sampled_images():
-    # the benchmark configuration: 32 layers, B=64, T=257; the checker recomputes two images
+    # the benchmark configuration: 32 layers, B=64, T=257.  The checker recomputes eight images
+    # spread over the batch (one in each eighth: the attention kernel deals images 8k .. 8k+7 to
+    # one XCD, the dense layers one tile row per image), each compared element by element.
     sh = synth.SHAPES["vit_huge"]
     layers = layers_of(sh, 32, bf16=True, affine=False)
     st = H.make_stage(sh, layers, 0, 32, 64, bf16=True)
     x = synth.activations(sh, 64, bf16=True)
     got = H.run_stage(st, x)
     assert np.isfinite(got).all()
-    for i in (0, 63):
+    worst = 0.0
+    for i in (0, 9, 18, 27, 36, 45, 54, 63):
         ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x[i:i + 1])[0]
         e, s = H.rel_err(got[i], ref), H.err_std(got[i], ref)
-        print(f"ViT-Huge 32 layers B=64 image {i}: err {e:.3e}, std {s:.3e}, rms {math.sqrt((ref**2).mean()):.3f}")
-        assert e <= H.TOL_BF16
-    rms = np.sqrt((got.astype(np.float64) ** 2).mean(axis=(1, 2)))
-    assert np.all(np.abs(rms / rms[0] - 1) < 0.2)
+        print(f"ViT-Huge 32 layers B=64 image {i}: err {e:.3e}, std {s:.3e}, rms {math.sqrt((ref**2).mean()):.3f}",
+              flush=True)
+        worst = max(worst, e)
+    assert worst <= H.TOL_BF16
+    # Every image, every position: the same images dealt to other positions of the batch (rolled by
+    # 9: another XCD range, another tile row).  A row of a dense layer, a row of LayerNorm and an
+    # (image, head) pair of attention are computed by the same instruction sequence wherever they
+    # sit, so the results are bit-identical - except for the image in the last position, whose last
+    # 64 rows are the row remainder and take the narrow tiles (another summation order).
+    shift = 9
+    got_r = H.run_stage(st, np.roll(x, shift, axis=0))
+    for i in range(64):
+        j = (i + shift) % 64
+        if i == 63 or j == 63:
+            e = H.rel_err(got_r[j], got[i])
+            assert e <= H.TOL_BF16, (i, j, e)
+        else:
+            np.testing.assert_array_equal(got_r[j], got[i], err_msg=f"image {i} at position {j}")
     # 64 * 257 rows = 64 tiles of 256 rows + 64: every dense layer runs as one persistent launch
     # whose last phase takes the 64 remaining rows
     for name, kid in binding.MAIN_KERNEL_IDS.items():
         assert st.gemm_main_rows(64, kid) == 16448
+    st.destroy()
 
 
 @pytest.mark.parametrize("name,batch", [("deit_tiny", 32), ("deit_small", 16), ("deit_small", 256)])
@@ -343,9 +372,10 @@ def test_profile_and_trace_report_positive_times():
 
 def test_heterogeneous_partition_stages_match_checker():
     """Per-layer costs profiled on this GPU feed ep_partition for 16 synthetic devices
-    (seed 1); every resulting uneven stage is run at several micro-batch sizes and
+    (seed 1); every resulting uneven stage is run at micro-batches 1, 2, 4, ..., 256 and
     compared with the checker on image 0 (images are independent, so one reference per
-    stage serves every batch size) and on the last image of the largest batch."""
+    stage serves every batch size) and on the last image of every batch; then the stages
+    are chained and compared with the checker's result over all 32 layers."""
     from oracle import partition as P
     sh = synth.SHAPES["vit_huge"]
     B_plan = 8
@@ -362,22 +392,43 @@ def test_heterogeneous_partition_stages_match_checker():
     sizes = [l - f + 1 for _, f, l in plan]
     print(f"plan: T_opt={t_opt:.4f}s, stages (device, first, last): {plan}")
     assert sum(sizes) == 32 and len(set(sizes)) > 1         # uneven stages
-    batches = (1, 4, 32, 256)
+    batches = (1, 2, 4, 8, 16, 32, 64, 128, 256)
     for s_idx, (_dev, first, last) in enumerate(plan):
         stage_layers = layers[first:last + 1]
         st = H.make_stage(sh, stage_layers, first, last + 1, max(batches), bf16=True)
         tag = f"stage{s_idx}"                              # independent N(0,1) input per stage
-        ref0 = oracle.stage_forward(H.oracle_cfg(sh), stage_layers,
-                                    synth.activations(sh, 1, bf16=True, tag=tag))[0]
+        x_all = synth.activations(sh, max(batches), bf16=True, tag=tag)   # image i is the same in every batch
+        ref0 = oracle.stage_forward(H.oracle_cfg(sh), stage_layers, x_all[:1])[0]
         for B in batches:
-            x = synth.activations(sh, B, bf16=True, tag=tag)
-            got = H.run_stage(st, x)
+            got = H.run_stage(st, x_all[:B])
             assert np.isfinite(got).all()
             e = H.rel_err(got[0], ref0)
             assert e <= H.TOL_BF16, (s_idx, B, e)
-            if B == max(batches):
-                ref_last = oracle.stage_forward(H.oracle_cfg(sh), stage_layers, x[B - 1:B])[0]
+            if B > 1:
+                # the last image of the batch: at B = 256 its rows are the ones past the tile walk
+                ref_last = oracle.stage_forward(H.oracle_cfg(sh), stage_layers, x_all[B - 1:B])[0]
                 e2 = H.rel_err(got[B - 1], ref_last)
-                print(f"stage {s_idx} layers {first}-{last}: B={B} image 0 err {e:.2e}, image {B-1} err {e2:.2e}")
-                assert e2 <= H.TOL_BF16
+                print(f"stage {s_idx} layers {first}-{last}: B={B} image 0 err {e:.2e}, image {B-1} err {e2:.2e}",
+                      flush=True)
+                assert e2 <= H.TOL_BF16, (s_idx, B, e2)
         st.destroy()
+
+    # The plan's stages chained (fp32 boundaries, micro-batch 2): stage k's output is stage k+1's
+    # input, the last output is compared with the checker's result over all 32 layers.
+    import torch
+    B = 2
+    x = synth.activations(sh, B, bf16=True)
+    cur = H.to_device(x, True)
+    for s_idx, (_dev, first, last) in enumerate(plan):
+        st = H.make_stage(sh, layers[first:last + 1], first, last + 1, B, bf16=True, in_bf16=(s_idx == 0))
+        nxt = torch.empty(x.shape, dtype=torch.float32, device="cuda")
+        st.forward(cur, B, nxt, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        st.destroy()
+        cur = nxt
+    got = cur.cpu().numpy()
+    ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x)
+    for i in range(B):
+        e = H.rel_err(got[i], ref[i])
+        print(f"chained plan, {len(plan)} stages, B={B}, image {i}: err {e:.3e}, std {H.err_std(got[i], ref[i]):.3e}")
+        assert e <= H.TOL_BF16

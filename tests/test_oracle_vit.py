@@ -295,3 +295,81 @@ def test_rounding_mode_is_small_perturbation_and_off_by_default():
     rms = math.sqrt((exact ** 2).mean())
     err = np.abs(exact - rounded).max() / rms
     assert 0 < err < 2e-2
+
+
+# ------------------------------------------- the diagnostic mode's bf16 narrowing
+def test_round_bf16_ties_go_to_even_and_signs_mirror():
+    # bf16 keeps 8 significant bits: neighbours of 1 are 1 - 2^-8 and 1 + 2^-7
+    r = oracle.round_bf16
+    assert r(1.0) == 1.0 and r(0.0) == 0.0 and r(-0.0) == 0.0 and math.copysign(1.0, r(-0.0)) == -1.0
+    assert r(1 + 2.0 ** -8) == 1.0                        # halfway between 1 (even) and 1 + 2^-7 (odd)
+    assert r(1 + 3 * 2.0 ** -8) == 1 + 2.0 ** -6          # halfway between 1 + 2^-7 (odd) and 1 + 2^-6 (even)
+    assert r(1 + 2.0 ** -8 + 2.0 ** -20) == 1 + 2.0 ** -7   # just above the tie: up
+    assert r(1 + 2.0 ** -8 - 2.0 ** -20) == 1.0             # just below: down
+    assert r(1 + 5 * 2.0 ** -8) == 1 + 2.0 ** -6          # tie between 1 + 2^-6 (even) and 1 + 3*2^-7 (odd)
+    for v in (1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8, 1 + 2.0 ** -8 + 2.0 ** -20, 3.14159, 1e-3, 2.5e20):
+        assert r(-v) == -r(v)
+    # truncation would give 1 + 2^-7 here, rounding half up the same, half-to-even too: a plain value
+    assert r(1 + 2.0 ** -7 + 2.0 ** -9) == 1 + 2.0 ** -7
+    # a carry out of the mantissa moves to the next binade
+    assert r(2 - 2.0 ** -9) == 2.0
+    assert r(2 - 2.0 ** -8) == 2.0                        # tie: 2 - 2^-7 is odd, 2 is even
+    assert r(2 - 3 * 2.0 ** -9) == 2 - 2.0 ** -7
+
+
+def test_round_bf16_narrows_through_float32_first():
+    # 1 + 2^-8 + 2^-30 lies above the tie, but float32 (24 significant bits) cannot hold the 2^-30:
+    # the value is narrowed to float32 first, lands exactly on the tie, and goes to the even side.
+    # Rounding the float64 value to bf16 in one step would give 1 + 2^-7 instead.
+    assert oracle.round_bf16(1 + 2.0 ** -8 + 2.0 ** -30) == 1.0
+    assert oracle.round_bf16(1 + 3 * 2.0 ** -8 - 2.0 ** -30) == 1 + 2.0 ** -6
+
+
+def test_round_bf16_special_values_and_range():
+    r = oracle.round_bf16
+    assert r(math.inf) == math.inf and r(-math.inf) == -math.inf
+    assert math.isnan(r(math.nan))
+    big = float(np.finfo(np.float32).max)                 # above the largest bf16, past its tie: infinity
+    assert r(big) == math.inf and r(-big) == -math.inf
+    largest = (2 - 2.0 ** -7) * 2.0 ** 127                # the largest finite bf16
+    assert r(largest) == largest
+    tiny = 2.0 ** -133                                    # a bf16 subnormal (multiples of 2^-133)
+    assert r(tiny) == tiny and r(1.5 * tiny) == 2 * tiny and r(2.5 * tiny) == 2 * tiny
+
+
+def test_round_bf16_agrees_with_library_conversion():
+    vals = np.concatenate([rnd("rb/a", 4000), rnd("rb/b", 2000) * 1e-4, rnd("rb/c", 2000) * 1e5,
+                           # exact ties and their neighbours at many exponents
+                           np.array([(1 + (2 * k + 1) * 2.0 ** -8) * 2.0 ** e for k in range(8) for e in (-20, -1, 0, 7)]),
+                           ]).astype(np.float32)
+    want = torch.from_numpy(vals).to(torch.bfloat16).to(torch.float64).numpy()
+    got = np.array([oracle.round_bf16(float(v)) for v in vals])
+    np.testing.assert_array_equal(got, want)
+
+
+def test_rounding_mode_narrows_exactly_the_five_operand_points():
+    # the layer rebuilt from the checker's own steps with the narrowing done by the library's
+    # float32 -> bf16 conversion at: both LayerNorm outputs, q|k|v, the attention probabilities
+    # (inside the attention step), the attention output and the GELU output
+    def nb(a):
+        return torch.from_numpy(np.asarray(a, dtype=np.float64)).to(torch.float32).to(torch.bfloat16) \
+            .to(torch.float64).numpy()
+    sh = small_shape(T=9, D=32, H=2, M=48, L=1)
+    p = synth.layer_params(sh, 0, bf16=True, randomize_affine=True, w_std=0.2)
+    x = synth.activations(sh, 2, bf16=True).astype(np.float64)
+    got = oracle.layer_forward(cfg_of(sh, round_mode=1), p, x)
+    out = np.empty_like(x)
+    for b in range(x.shape[0]):
+        y = nb(oracle.layernorm(x[b], p["ln1_g"], p["ln1_b"], sh.ln_eps))
+        qkv = nb(oracle.linear(y, p["w_qkv"], p["b_qkv"]))
+        o = nb(oracle.attention(qkv, sh.n_heads, round_mode=1))
+        x1 = x[b] + oracle.linear(o, p["w_o"], p["b_o"])
+        z = nb(oracle.layernorm(x1, p["ln2_g"], p["ln2_b"], sh.ln_eps))
+        h = nb(oracle.gelu(oracle.linear(z, p["w_fc1"], p["b_fc1"])))
+        out[b] = x1 + oracle.linear(h, p["w_fc2"], p["b_fc2"])
+    np.testing.assert_array_equal(got, out)
+    # and the probabilities: rounded after normalisation, before they weigh the values
+    qkv = rnd("rm/qkv", 5, 3 * 8)
+    o_r = oracle.attention(qkv, 1, round_mode=1)
+    _, pr = oracle.attention(qkv, 1, return_probs=True)
+    np.testing.assert_allclose(o_r, nb(pr[0]) @ qkv[:, 16:], rtol=1e-13, atol=1e-15)
