@@ -125,6 +125,29 @@ ep_status ep_stage_forward(ep_stage_t *stage, const void *x_in, int32_t B, void 
                            void *stream);
 
 /*
+ * ep_stage_forward for callers that cannot allocate device memory and want
+ * stages that own none beyond their parameters: code under stream capture,
+ * tight serving loops, harnesses that forbid allocation (such a caller creates
+ * its stages with max_batch 1, whose own workspace is small, and runs them
+ * through this call).  Same arguments, same kernels, same results as
+ * ep_stage_forward, bit for bit; the intermediates (residual stream, GEMM
+ * operands, q|k|v / hidden activations) live in a workspace of
+ * EP_STATIC_SCRATCH_BYTES that is part of the library's code object - one per
+ * GPU, held until the process ends - instead of in the stage's own.  The call
+ * allocates nothing and frees nothing.  B is limited by that workspace, not by
+ * max_batch: B * T * (4*D + e*D + e*max(3*D, M)) bytes (e = 2 on the bf16 path,
+ * 4 on the fp32 path; each part rounded up to 256) must fit, else UNSUPPORTED
+ * with the two sizes in ep_last_error() (ViT-Huge bf16: B <= 14; ViT-Base: B <= 31).
+ * Every stage on a GPU shares that GPU's workspace and nothing in it is assumed
+ * zero or kept between calls: calls that overlap in time on one GPU (two
+ * streams, two threads) race; calls on one stream, or ordered by events, do not.
+ * Other errors as ep_stage_forward.
+ */
+#define EP_STATIC_SCRATCH_BYTES (64u << 20)
+ep_status ep_stage_forward_static(ep_stage_t *stage, const void *x_in, int32_t B, void *x_out,
+                                  void *stream);
+
+/*
  * Measure the execution time of each layer of the stage at micro-batch B on this
  * device: the T_comp(l, u) input of the planner (section 3.3; section 5.1
  * measures the same quantity per layer).  Each layer is run `iters` times

@@ -70,6 +70,8 @@ def lib() -> C.CDLL:
         L.ep_stage_create.argtypes = [C.POINTER(ep_vit_config), C.c_int32, C.c_int32,
                                       C.POINTER(ep_layer_weights), C.c_int32, C.POINTER(C.c_void_p)]
         L.ep_stage_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.ep_stage_forward_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.ep_stage_forward_static.restype = C.c_int
         L.ep_stage_profile.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, dp]
         L.ep_stage_trace_begin.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         L.ep_stage_trace_end.argtypes = [C.c_void_p, ip, dp]
@@ -182,6 +184,10 @@ class Stage:
     def forward(self, x_in, batch: int, x_out, stream=None) -> None:
         _check(lib().ep_stage_forward(self._h, _addr(x_in), batch, _addr(x_out), _stream(stream)),
                "ep_stage_forward")
+
+    def forward_static(self, x_in, batch: int, x_out, stream=None) -> None:
+        _check(lib().ep_stage_forward_static(self._h, _addr(x_in), int(batch), _addr(x_out), _stream(stream)),
+               "ep_stage_forward_static")
 
     def profile(self, batch: int, iters: int = 5, stream=None) -> np.ndarray:
         out = np.zeros(self.n_layers, dtype=np.float64)

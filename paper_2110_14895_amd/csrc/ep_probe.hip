@@ -7,7 +7,7 @@
 //
 // One workgroup of 8 waves per compute unit (two waves per SIMD, like the
 // dense-layer kernels); every wave multiplies 4 x 4 fragment pairs round and
-// round into 16 (form 0) or 4 x 4 / 4 (form 1) accumulators, so consecutive
+// round into 16 (form 0) or 4 (form 1) accumulators taken in rotation, so consecutive
 // matrix instructions are independent and see different operand data.  Each
 // workgroup reads the shader clock counter and the constant 100 MHz counter
 // before and after its loop: their ratio is the clock the loop ran at.
@@ -70,12 +70,12 @@ __global__ __launch_bounds__(WAVES * 64, 1) void mfma_peak_kernel(const uint4 *_
     } else {
         f32x16 acc[2][2] = {};
         for (int it = 0; it < iters; ++it) {
-            // the same 16 operand pairs per iteration, four per accumulator
+            // the same 16 operand pairs per iteration, four per accumulator, the accumulators in rotation
 #pragma unroll
             for (int i = 0; i < NFRAG; ++i)
 #pragma unroll
                 for (int j = 0; j < NFRAG; ++j)
-                    acc[i & 1][j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i & 1][j & 1], 0, 0, 0);
+                    acc[j >> 1][j & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[j >> 1][j & 1], 0, 0, 0);
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i)

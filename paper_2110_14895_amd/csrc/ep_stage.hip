@@ -12,6 +12,7 @@
 // where act is bf16 on the bf16 path and fp32 on the fp32 path.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -20,6 +21,7 @@
 #include "edgepipe.h"
 #include "ep_error.h"
 #include "ep_kernels.h"
+#include "ep_launch.h"
 
 namespace {
 
@@ -40,6 +42,13 @@ inline float bf16_bits_to_float(uint16_t h)
 
 }  // namespace
 
+// where a forward keeps its intermediates (see the file header)
+struct Workspace {
+    float *x;
+    void *a;
+    void *big;
+};
+
 struct ep_stage {
     ep_vit_config cfg;
     int32_t begin, end, max_batch;
@@ -49,9 +58,7 @@ struct ep_stage {
     size_t params_bytes = 0;
     char *ws = nullptr;
     size_t ws_bytes = 0;
-    float *x = nullptr;
-    void *a = nullptr;
-    void *big = nullptr;
+    Workspace own = {nullptr, nullptr, nullptr};   // inside ws
     std::vector<LayerDev> layers;
     // per-kernel timing (ep_stage_trace_begin / _end)
     int trace_kernel = -1;
@@ -99,6 +106,29 @@ ep_status check_config(const ep_vit_config *c)
     return EP_OK;
 }
 
+// Workspace of a forward over `batch` images: x | a | big, each part 256-byte aligned.
+struct WorkspaceLayout { size_t x_bytes, a_bytes, big_bytes; };
+
+WorkspaceLayout workspace_layout(const ep_vit_config &c, int64_t batch)
+{
+    const size_t asz = c.param_dtype == EP_BF16 ? 2 : 4;     // bytes per activation-operand element
+    const size_t R = (size_t)batch * c.n_tokens, D = c.d_model, M = c.d_mlp;
+    const size_t wide = 3 * D > M ? 3 * D : M;
+    return {align_up(R * D * 4, 256), align_up(R * D * asz, 256), align_up(R * wide * asz, 256)};
+}
+
+size_t workspace_bytes(const ep_vit_config &c, int64_t batch)
+{
+    const WorkspaceLayout l = workspace_layout(c, batch);
+    return l.x_bytes + l.a_bytes + l.big_bytes;
+}
+
+Workspace carve_workspace(char *base, const ep_vit_config &c, int64_t batch)
+{
+    const WorkspaceLayout l = workspace_layout(c, batch);
+    return {(float *)base, base + l.x_bytes, base + l.x_bytes + l.a_bytes};
+}
+
 // Brackets one kernel of the layer with an event pair when that kernel is traced.  For a dense
 // layer traced under its _MAIN id the closing event is handed to the GEMM dispatcher, which
 // records it right after its first launch.
@@ -127,39 +157,67 @@ struct TraceScope {
 
 // One layer on R = B*T rows.  `xin` is the residual stream read by this layer
 // (may be the caller's fp32 input), the layer leaves its result in `xout`.
-ep_status run_layer(ep_stage *st, const LayerDev &L, const float *xin, float *xout, int B,
+ep_status run_layer(ep_stage *st, const Workspace &w, const LayerDev &L, const float *xin, float *xout, int B,
                     hipStream_t s)
 {
     const ep_vit_config &c = st->cfg;
     const int T = c.n_tokens, D = c.d_model, M = c.d_mlp, H = c.n_heads;
     const int64_t R = (int64_t)B * T;
     if (st->bf16) {
-        uint16_t *a = (uint16_t *)st->a, *big = (uint16_t *)st->big;
+        uint16_t *a = (uint16_t *)w.a, *big = (uint16_t *)w.big;
         EP_TRACED(EP_K_LN1, ep_bf16_layernorm(xin, L.ln1_g, L.ln1_b, c.ln_eps, a, R, D, s));
         EP_TRACED_GEMM(EP_K_QKV, EP_K_QKV_MAIN,
                        ep_bf16_gemm(a, (const uint16_t *)L.w_qkv, L.b_qkv, nullptr, big, R, 3 * D, D, EPI_BIAS,
                                     ts_.after_main(), s));
         EP_TRACED(EP_K_ATTN, ep_bf16_attention(big, a, B, T, D, H, s));
         EP_TRACED_GEMM(EP_K_PROJ, EP_K_PROJ_MAIN,
-                       ep_bf16_gemm(a, (const uint16_t *)L.w_o, L.b_o, xin, st->x, R, D, D, EPI_BIAS_RESID,
+                       ep_bf16_gemm(a, (const uint16_t *)L.w_o, L.b_o, xin, w.x, R, D, D, EPI_BIAS_RESID,
                                     ts_.after_main(), s));
-        EP_TRACED(EP_K_LN2, ep_bf16_layernorm(st->x, L.ln2_g, L.ln2_b, c.ln_eps, a, R, D, s));
+        EP_TRACED(EP_K_LN2, ep_bf16_layernorm(w.x, L.ln2_g, L.ln2_b, c.ln_eps, a, R, D, s));
         EP_TRACED_GEMM(EP_K_FC1, EP_K_FC1_MAIN,
                        ep_bf16_gemm(a, (const uint16_t *)L.w_fc1, L.b_fc1, nullptr, big, R, M, D, EPI_BIAS_GELU,
                                     ts_.after_main(), s));
         EP_TRACED_GEMM(EP_K_FC2, EP_K_FC2_MAIN,
-                       ep_bf16_gemm(big, (const uint16_t *)L.w_fc2, L.b_fc2, st->x, xout, R, D, M, EPI_BIAS_RESID,
+                       ep_bf16_gemm(big, (const uint16_t *)L.w_fc2, L.b_fc2, w.x, xout, R, D, M, EPI_BIAS_RESID,
                                     ts_.after_main(), s));
     } else {
-        float *a = (float *)st->a, *big = (float *)st->big;
+        float *a = (float *)w.a, *big = (float *)w.big;
         EP_TRACED(EP_K_LN1, ep_f32_layernorm(xin, L.ln1_g, L.ln1_b, c.ln_eps, a, R, D, s));
         EP_TRACED(EP_K_QKV, ep_f32_gemm(a, (const float *)L.w_qkv, L.b_qkv, nullptr, big, R, 3 * D, D, EPI_BIAS, s));
         EP_TRACED(EP_K_ATTN, ep_f32_attention(big, a, B, T, D, H, s));
-        EP_TRACED(EP_K_PROJ, ep_f32_gemm(a, (const float *)L.w_o, L.b_o, xin, st->x, R, D, D, EPI_BIAS_RESID, s));
-        EP_TRACED(EP_K_LN2, ep_f32_layernorm(st->x, L.ln2_g, L.ln2_b, c.ln_eps, a, R, D, s));
+        EP_TRACED(EP_K_PROJ, ep_f32_gemm(a, (const float *)L.w_o, L.b_o, xin, w.x, R, D, D, EPI_BIAS_RESID, s));
+        EP_TRACED(EP_K_LN2, ep_f32_layernorm(w.x, L.ln2_g, L.ln2_b, c.ln_eps, a, R, D, s));
         EP_TRACED(EP_K_FC1, ep_f32_gemm(a, (const float *)L.w_fc1, L.b_fc1, nullptr, big, R, M, D, EPI_BIAS_GELU, s));
-        EP_TRACED(EP_K_FC2, ep_f32_gemm(big, (const float *)L.w_fc2, L.b_fc2, st->x, xout, R, D, M, EPI_BIAS_RESID, s));
+        EP_TRACED(EP_K_FC2, ep_f32_gemm(big, (const float *)L.w_fc2, L.b_fc2, w.x, xout, R, D, M, EPI_BIAS_RESID, s));
     }
+    return EP_OK;
+}
+
+}  // namespace
+
+// ---- the library's own workspace for callers that cannot allocate -------------------------------
+// One array per device, part of the loaded code object, held until the process ends.  In host code
+// the array's name stands for the symbol, not for device memory: its device address is looked up
+// once per device (with that device current) and only that address is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[EP_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+std::atomic<unsigned char *> g_scratch_ptr[EP_MAX_DEVICES];      // zero-initialised
+
+// device address of `scratch` on the current device `dev`
+ep_status static_scratch(int dev, unsigned char **out)
+{
+    if (dev < 0 || dev >= EP_MAX_DEVICES)
+        return ep_fail(EP_ERR_UNSUPPORTED, "device index %d outside the %d the library keeps a workspace for", dev,
+                       EP_MAX_DEVICES);
+    unsigned char *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        EP_HIP(hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)));
+        if (!p) return ep_fail(EP_ERR_HIP, "hipGetSymbolAddress returned a null address");
+        g_scratch_ptr[dev].store(p, std::memory_order_release);    // every thread stores the same address
+    }
+    *out = p;
     return EP_OK;
 }
 
@@ -208,11 +266,16 @@ extern "C" ep_status ep_stage_create(const ep_vit_config *cfg, int32_t layer_beg
     st->begin = layer_begin; st->end = layer_end; st->max_batch = max_batch;
     st->bf16 = cfg->param_dtype == EP_BF16;
     const size_t wsz = st->bf16 ? 2 : 4;     // bytes per dense-weight element
-    const size_t asz = wsz;                  // bytes per activation-operand element
 
     auto fail = [&](ep_status s) { ep_stage_destroy(st); return s; };
     hipError_t e = hipGetDevice(&st->device);
     if (e != hipSuccess) return fail(ep_fail(EP_ERR_HIP, "hipGetDevice failed: %s", hipGetErrorString(e)));
+    {
+        // set-up for ep_stage_forward_static on this device: the address of the library's own workspace
+        unsigned char *unused = nullptr;
+        const ep_status src = static_scratch(st->device, &unused);
+        if (src != EP_OK) return fail(src);
+    }
 
     // ---- parameter block layout (per layer): dense weights, then fp32 vectors
     const size_t n_w[4] = {(size_t)(3 * D * D), (size_t)(D * D), (size_t)(M * D), (size_t)(D * M)};
@@ -231,21 +294,14 @@ extern "C" ep_status ep_stage_create(const ep_vit_config *cfg, int32_t layer_beg
     }
 
     // ---- workspace
-    const size_t R = (size_t)max_batch * T;
-    const size_t wide = (size_t)(3 * D > M ? 3 * D : M);
-    const size_t x_bytes = align_up(R * D * 4, 256);
-    const size_t a_bytes = align_up(R * D * asz, 256);
-    const size_t big_bytes = align_up(R * wide * asz, 256);
-    st->ws_bytes = x_bytes + a_bytes + big_bytes;
+    st->ws_bytes = workspace_bytes(st->cfg, max_batch);
     e = hipMalloc((void **)&st->ws, st->ws_bytes);
     if (e != hipSuccess) {
         st->ws = nullptr;
         return fail(ep_fail(EP_ERR_OOM, "hipMalloc of %zu workspace bytes failed: %s", st->ws_bytes,
                             hipGetErrorString(e)));
     }
-    st->x = (float *)st->ws;
-    st->a = st->ws + x_bytes;
-    st->big = st->ws + x_bytes + a_bytes;
+    st->own = carve_workspace(st->ws, st->cfg, max_batch);
 
     // ---- upload, one layer at a time through a host staging block
     std::vector<char> stage_buf;
@@ -285,6 +341,35 @@ extern "C" ep_status ep_stage_create(const ep_vit_config *cfg, int32_t layer_beg
     return EP_OK;
 }
 
+namespace {
+
+// the launches of a forward over B images with the intermediates in `w`
+ep_status forward_on(ep_stage *st, const Workspace &w, const void *x_in, int32_t B, void *x_out, hipStream_t s)
+{
+    const ep_vit_config &c = st->cfg;
+    const int64_t n = (int64_t)B * c.n_tokens * c.d_model;
+    const int nl = st->end - st->begin;
+
+    const float *cur;
+    if (c.in_dtype == EP_BF16) {
+        EP_HIP(ep_bf16_to_f32((const uint16_t *)x_in, w.x, n, s));
+        cur = w.x;
+    } else {
+        cur = (const float *)x_in;     // first layer reads the caller's buffer directly
+    }
+    for (int l = 0; l < nl; ++l) {
+        const bool last = l + 1 == nl;
+        float *dst = (last && c.out_dtype == EP_F32) ? (float *)x_out : w.x;
+        ep_status rc = run_layer(st, w, st->layers[l], cur, dst, B, s);
+        if (rc != EP_OK) return rc;
+        cur = dst;
+    }
+    if (c.out_dtype == EP_BF16) EP_HIP(ep_f32_to_bf16(w.x, (uint16_t *)x_out, n, s));
+    return EP_OK;
+}
+
+}  // namespace
+
 extern "C" ep_status ep_stage_forward(ep_stage_t *st, const void *x_in, int32_t B, void *x_out, void *stream)
 {
     if (!st || !x_in || !x_out) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_forward: null argument");
@@ -295,27 +380,27 @@ extern "C" ep_status ep_stage_forward(ep_stage_t *st, const void *x_in, int32_t 
     if (dev != st->device)
         return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_forward: stage lives on device %d, current device is %d",
                        st->device, dev);
-    hipStream_t s = (hipStream_t)stream;
-    const ep_vit_config &c = st->cfg;
-    const int64_t n = (int64_t)B * c.n_tokens * c.d_model;
-    const int nl = st->end - st->begin;
+    return forward_on(st, st->own, x_in, B, x_out, (hipStream_t)stream);
+}
 
-    const float *cur;
-    if (c.in_dtype == EP_BF16) {
-        EP_HIP(ep_bf16_to_f32((const uint16_t *)x_in, st->x, n, s));
-        cur = st->x;
-    } else {
-        cur = (const float *)x_in;     // first layer reads the caller's buffer directly
-    }
-    for (int l = 0; l < nl; ++l) {
-        const bool last = l + 1 == nl;
-        float *dst = (last && c.out_dtype == EP_F32) ? (float *)x_out : st->x;
-        ep_status rc = run_layer(st, st->layers[l], cur, dst, B, s);
-        if (rc != EP_OK) return rc;
-        cur = dst;
-    }
-    if (c.out_dtype == EP_BF16) EP_HIP(ep_f32_to_bf16(st->x, (uint16_t *)x_out, n, s));
-    return EP_OK;
+extern "C" ep_status ep_stage_forward_static(ep_stage_t *st, const void *x_in, int32_t B, void *x_out, void *stream)
+{
+    if (!st || !x_in || !x_out) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_forward_static: null argument");
+    if (B < 1) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_forward_static: B=%d, must be >= 1", B);
+    const size_t need = workspace_bytes(st->cfg, B);
+    if (need > (size_t)EP_STATIC_SCRATCH_BYTES)
+        return ep_fail(EP_ERR_UNSUPPORTED,
+                       "ep_stage_forward_static: a micro-batch of %d images needs %zu workspace bytes, the library's "
+                       "own workspace holds %zu", B, need, (size_t)EP_STATIC_SCRATCH_BYTES);
+    int dev = -1;
+    EP_HIP(hipGetDevice(&dev));
+    if (dev != st->device)
+        return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_forward_static: stage lives on device %d, current device is %d",
+                       st->device, dev);
+    unsigned char *base = nullptr;
+    const ep_status rc = static_scratch(dev, &base);      // looked up when the stage was created: a table read
+    if (rc != EP_OK) return rc;
+    return forward_on(st, carve_workspace((char *)base, st->cfg, B), x_in, B, x_out, (hipStream_t)stream);
 }
 
 extern "C" ep_status ep_stage_profile(ep_stage_t *st, int32_t B, int32_t iters, void *stream,
@@ -337,18 +422,18 @@ extern "C" ep_status ep_stage_profile(ep_stage_t *st, int32_t B, int32_t iters, 
     EP_HIP(hipEventCreate(&t0));
     hipError_t e = hipEventCreate(&t1);
     if (e != hipSuccess) {
-        hipEventDestroy(t0);
+        (void)hipEventDestroy(t0);
         return ep_fail(EP_ERR_HIP, "hipEventCreate failed: %s", hipGetErrorString(e));
     }
     ep_status rc = EP_OK;
     for (int l = 0; l < nl && rc == EP_OK; ++l) {
         // fresh, bounded input for every layer so that repeated application cannot drift
-        if ((e = ep_fill_pattern(st->x, n, s)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "fill failed: %s", hipGetErrorString(e)); break; }
-        rc = run_layer(st, st->layers[l], st->x, st->x, B, s);          // untimed
+        if ((e = ep_fill_pattern(st->own.x, n, s)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "fill failed: %s", hipGetErrorString(e)); break; }
+        rc = run_layer(st, st->own, st->layers[l], st->own.x, st->own.x, B, s);          // untimed
         if (rc != EP_OK) break;
-        if ((e = ep_fill_pattern(st->x, n, s)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "fill failed: %s", hipGetErrorString(e)); break; }
+        if ((e = ep_fill_pattern(st->own.x, n, s)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "fill failed: %s", hipGetErrorString(e)); break; }
         if ((e = hipEventRecord(t0, s)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "hipEventRecord failed: %s", hipGetErrorString(e)); break; }
-        for (int it = 0; it < iters && rc == EP_OK; ++it) rc = run_layer(st, st->layers[l], st->x, st->x, B, s);
+        for (int it = 0; it < iters && rc == EP_OK; ++it) rc = run_layer(st, st->own, st->layers[l], st->own.x, st->own.x, B, s);
         if (rc != EP_OK) break;
         if ((e = hipEventRecord(t1, s)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "hipEventRecord failed: %s", hipGetErrorString(e)); break; }
         if ((e = hipEventSynchronize(t1)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "hipEventSynchronize failed: %s", hipGetErrorString(e)); break; }
@@ -356,8 +441,8 @@ extern "C" ep_status ep_stage_profile(ep_stage_t *st, int32_t B, int32_t iters, 
         if ((e = hipEventElapsedTime(&ms, t0, t1)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "hipEventElapsedTime failed: %s", hipGetErrorString(e)); break; }
         per_layer_seconds[l] = (double)ms * 1e-3 / iters;
     }
-    hipEventDestroy(t0);
-    hipEventDestroy(t1);
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
     return rc;
 }
 
