@@ -224,6 +224,16 @@ ep_status ep_stage_gemm_main_rows(const ep_stage_t *stage, int32_t B, int32_t ke
 ep_status ep_mfma_peak(int32_t form, int32_t random_operands, int32_t iters, void *stream,
                        double *tflops, double *shader_mhz);
 
+/*
+ * Measurement hook: the shader clock the most recent large dense-layer launch
+ * (one resident workgroup per compute unit; the launches ep_stage_forward makes
+ * for micro-batches that fill the chip) ran at on the current device, and how
+ * long its first workgroup ran: that workgroup reads the shader cycle counter
+ * and the 100 MHz counter when it starts and when it ends.  Synchronise the
+ * stream first.  Outputs HOST.  INVALID_ARG if no such launch has finished.
+ */
+ep_status ep_gemm_clock_sample(double *shader_mhz, double *seconds);
+
 /* Configuration, layer range and max_batch the stage was created with (HOST outputs,
  * each may be NULL). */
 ep_status ep_stage_info(const ep_stage_t *stage, ep_vit_config *cfg, int32_t *layer_begin,

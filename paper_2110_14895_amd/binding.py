@@ -94,6 +94,8 @@ def lib() -> C.CDLL:
         L.ep_stage_destroy.argtypes = [C.c_void_p]
         L.ep_stage_destroy.restype = None
         L.ep_mfma_peak.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, dp, dp]
+        L.ep_gemm_clock_sample.argtypes = [dp, dp]
+        L.ep_gemm_clock_sample.restype = C.c_int
         L.ep_partition.argtypes = [C.c_int32, C.c_int32, dp, dp, dp, dp, dp, dp, ip, ip, ip, ip]
         L.ep_partition_categories.argtypes = [C.c_int32, C.c_int32, dp, dp, dp, dp, dp, dp, ip, ip, ip, ip, ip]
         L.ep_status_string.argtypes = [C.c_int]
@@ -322,6 +324,13 @@ def mfma_peak(form: int, random_operands: bool, iters: int, stream=None) -> Tupl
     _check(lib().ep_mfma_peak(int(form), int(bool(random_operands)), int(iters), _stream(stream),
                               C.byref(tf), C.byref(mhz)), "ep_mfma_peak")
     return tf.value, mhz.value
+
+
+def gemm_clock_sample() -> Tuple[float, float]:
+    """(shader MHz, seconds) of workgroup 0 of the most recent large dense-layer launch that finished."""
+    mhz, sec = C.c_double(), C.c_double()
+    _check(lib().ep_gemm_clock_sample(C.byref(mhz), C.byref(sec)), "ep_gemm_clock_sample")
+    return mhz.value, sec.value
 
 
 def partition_categories(t_comp, layer_mem, dev_mem, xfer_bytes, bw):

@@ -101,6 +101,15 @@ struct Tile {
 typedef Tile<256, 2, 4> Tile256;                     // wave tile 128 x 64
 typedef Tile<320, 4, 2> Tile320;                     // wave tile 64 x 160
 
+}  // namespace
+
+// Measurement: the shader-cycle counter and the constant 100 MHz counter read by workgroup 0 at the
+// start ([0], [1]) and at the end ([2], [3]) of the most recent launch on this device; their ratio
+// is the shader clock that launch ran at (ep_gemm_clock_sample).
+static __device__ unsigned long long g_clock_sample[4];
+
+namespace {
+
 #define EP_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0 | (0x0 << 14) | (0x7 << 4) | (0xF << 8))
 #define EP_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8))
 #define EP_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -123,6 +132,10 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: wave-derived addressing stays scalar
+    if (blockIdx.x == 0 && tid == 0) {
+        g_clock_sample[0] = clock64();
+        g_clock_sample[1] = wall_clock64();
+    }
     const int wm0 = (wave / WN) * (MI * 32), wn0 = (wave % WN) * (NI * 32);
 
     // ---- this workgroup's tile list: tile j has logical id j*G + (w%8)*(G/8) + w/8
@@ -451,6 +464,10 @@ __global__ __launch_bounds__(NW * 64, 1) void gemm_bf16_persistent_kernel(
             __syncthreads();
         }
     }
+    if (blockIdx.x == 0 && tid == 0) {
+        g_clock_sample[2] = clock64();
+        g_clock_sample[3] = wall_clock64();
+    }
 #endif
 }
 
@@ -523,6 +540,18 @@ int64_t tile_cost(int64_t rows, int N, int bn, int cus)
 }
 
 }  // namespace
+
+hipError_t ep_bf16_gemm_persistent_clock(double *shader_mhz, double *seconds)
+{
+    unsigned long long h[4] = {0, 0, 0, 0};
+    const hipError_t e = hipMemcpyFromSymbol(h, HIP_SYMBOL(g_clock_sample), sizeof(h));
+    if (e != hipSuccess) return e;
+    const double cycles = (double)(h[2] - h[0]), ticks = (double)(h[3] - h[1]);     // ticks of 10 ns
+    if (h[3] <= h[1] || h[2] <= h[0]) return hipErrorNotReady;      // no launch has finished on this device yet
+    *shader_mhz = cycles / ticks * 100.0;
+    *seconds = ticks * 1e-8;
+    return hipSuccess;
+}
 
 bool ep_bf16_gemm_persistent_supported(int64_t M, int N, int K)
 {

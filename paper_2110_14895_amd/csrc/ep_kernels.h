@@ -59,6 +59,10 @@ hipError_t ep_bf16_gemm_persistent(const uint16_t *A, const uint16_t *W, const f
                                    const float *resid, void *C, int64_t M, int64_t m_rows, int N,
                                    int K, int epi, int tile_bn, bool fuse_tail, hipStream_t s);
 
+// Shader clock (MHz) and duration of workgroup 0 of the most recent persistent launch that has finished on the
+// current device (hipErrorNotReady if none has); copies four counters from the device, so it synchronises.
+hipError_t ep_bf16_gemm_persistent_clock(double *shader_mhz, double *seconds);
+
 // short-M kernel (ep_gemm_bf16_skinny.hip): 64 x 32 tiles, K dealt to the 8 waves of a workgroup
 bool ep_bf16_gemm_skinny_supported(int64_t M, int N, int K);
 hipError_t ep_bf16_gemm_skinny(const uint16_t *A, const uint16_t *W, const float *bias,

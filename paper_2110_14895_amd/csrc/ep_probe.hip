@@ -15,6 +15,7 @@
 
 #include "edgepipe.h"
 #include "ep_error.h"
+#include "ep_kernels.h"
 #include "ep_launch.h"
 
 namespace {
@@ -153,4 +154,14 @@ extern "C" ep_status ep_mfma_peak(int32_t form, int32_t random_operands, int32_t
     if (t1) (void)hipEventDestroy(t1);
     (void)hipFree(buf);
     return rc;
+}
+
+extern "C" ep_status ep_gemm_clock_sample(double *shader_mhz, double *seconds)
+{
+    if (!shader_mhz || !seconds) return ep_fail(EP_ERR_INVALID_ARG, "ep_gemm_clock_sample: null output");
+    const hipError_t e = ep_bf16_gemm_persistent_clock(shader_mhz, seconds);
+    if (e == hipErrorNotReady)
+        return ep_fail(EP_ERR_INVALID_ARG, "ep_gemm_clock_sample: no large dense-layer launch has finished on this device");
+    if (e != hipSuccess) return ep_fail(EP_ERR_HIP, "reading the clock sample failed: %s", hipGetErrorString(e));
+    return EP_OK;
 }
