@@ -61,8 +61,8 @@ typedef enum { EP_F32 = 0, EP_BF16 = 1 } ep_dtype;
  *             softmax, and the residual stream are fp32.  in_dtype / out_dtype
  *             choose bf16 or fp32 for the stage input / output (fp32 output
  *             keeps the residual stream un-rounded across stage boundaries).
- *             Requires D % 64 == 0, M % 64 == 0, d_head in {64, 80},
- *             T <= 288.
+ *             Requires D % 64 == 0, D <= 2048, M % 64 == 0, d_head in
+ *             {64, 80}, T <= 4096.
  */
 typedef struct {
     int32_t n_layers;    /* L */

@@ -20,6 +20,10 @@ LIB = os.path.join(HERE, "libedgepipe.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC, "-Wall", "-Wno-unused-function"]
 HIP_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+# Per-file additions.  The attention kernel takes maxima of matrix-pipe results; without the
+# promise that the compiler need not quiet signalling NaNs it doubles every one of them with a
+# canonicalising v_max (the hardware maxima and everything else stay IEEE: a NaN score still ends in NaN).
+FILE_FLAGS = {"ep_attn_bf16.hip": ["-fno-honor-nans"]}
 
 
 def sources():
@@ -28,7 +32,7 @@ def sources():
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, src.rsplit(".", 1)[0] + ".o")
-    cmd = [HIPCC] + COMMON + HIP_FLAGS + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC] + COMMON + HIP_FLAGS + FILE_FLAGS.get(src, []) + ["-c", os.path.join(CSRC, src), "-o", obj]
     if src.endswith(".cpp"):
         cmd.insert(1, "-x")
         cmd.insert(2, "hip")

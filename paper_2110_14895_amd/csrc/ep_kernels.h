@@ -34,7 +34,7 @@ hipError_t ep_bf16_gemm(const uint16_t *A, const uint16_t *W, const float *bias,
                         const float *resid, void *C, int64_t M, int N, int K, int epi,
                         hipEvent_t after_main, hipStream_t s);
 int64_t ep_bf16_gemm_main_rows(int64_t M, int N, int K);
-// qkv bf16 [B*T, 3D] -> o bf16 [B*T, D]
+// qkv bf16 [B*T, 3D] -> o bf16 [B*T, D]; d_head 64 or 80, T <= 4096 (K and V stream through LDS in chunks)
 hipError_t ep_bf16_attention(const uint16_t *qkv, uint16_t *o, int B, int T, int D, int H,
                              hipStream_t s);
 bool ep_bf16_attention_supported(int T, int d_head);

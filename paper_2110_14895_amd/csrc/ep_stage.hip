@@ -100,7 +100,7 @@ ep_status check_config(const ep_vit_config *c)
             return ep_fail(EP_ERR_UNSUPPORTED, "bf16 path supports d_model <= 2048");
         if (!ep_bf16_attention_supported(c->n_tokens, dh))
             return ep_fail(EP_ERR_UNSUPPORTED,
-                           "bf16 attention supports d_head in {64, 80} and n_tokens <= 288 (got %d, %d)",
+                           "bf16 attention supports d_head in {64, 80} and n_tokens <= 4096 (got %d, %d)",
                            dh, c->n_tokens);
     }
     return EP_OK;

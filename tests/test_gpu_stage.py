@@ -60,6 +60,11 @@ SMALL_BF16 = [
     (33, 128, 2, 192, 5),
     (1, 128, 2, 128, 1),
     (288, 128, 2, 256, 1),
+    # more tokens than one pass of ten query waves covers (320): the query tiles go in passes, the keys
+    # stream through once per pass; 577 = a 384 x 384 image in 16 x 16 patches plus the class token
+    (321, 128, 2, 128, 2),
+    (577, 320, 4, 192, 2),
+    (1000, 128, 2, 128, 1),
 ]
 
 
@@ -287,8 +292,9 @@ def test_vit_huge_all_layers_batch_64_sampled_images():
     got = H.run_stage(st, x)
     assert np.isfinite(got).all()
     worst = 0.0
+    refs = {}
     for i in (0, 9, 18, 27, 36, 45, 54, 63):
-        ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x[i:i + 1])[0]
+        ref = refs[i] = oracle.stage_forward(H.oracle_cfg(sh), layers, x[i:i + 1])[0]
         e, s = H.rel_err(got[i], ref), H.err_std(got[i], ref)
         print(f"ViT-Huge 32 layers B=64 image {i}: err {e:.3e}, std {s:.3e}, rms {math.sqrt((ref**2).mean()):.3f}",
               flush=True)
@@ -298,13 +304,16 @@ def test_vit_huge_all_layers_batch_64_sampled_images():
     # 9: another XCD range, another tile row).  A row of a dense layer, a row of LayerNorm and an
     # (image, head) pair of attention are computed by the same instruction sequence wherever they
     # sit, so the results are bit-identical - except for the image in the last position, whose last
-    # 64 rows are the row remainder and take the narrow tiles (another summation order).
+    # 64 rows are the row remainder and take the narrow tiles (another summation order): the two
+    # images that meet that position in one of the runs (63, and 54 after the roll) are held against
+    # the checker there instead.
     shift = 9
     got_r = H.run_stage(st, np.roll(x, shift, axis=0))
     for i in range(64):
         j = (i + shift) % 64
         if i == 63 or j == 63:
-            e = H.rel_err(got_r[j], got[i])
+            e = H.rel_err(got_r[j], refs[i])
+            print(f"image {i} at position {j}: err {e:.3e}")
             assert e <= H.TOL_BF16, (i, j, e)
         else:
             np.testing.assert_array_equal(got_r[j], got[i], err_msg=f"image {i} at position {j}")
