@@ -265,8 +265,12 @@ hipError_t launch_epi(const uint16_t *A, const uint16_t *W, const float *bias, c
 
 }  // namespace
 
-// The small-problem kernel: 128 x 128 tiles, K step 64, two stages, 4 waves, two workgroups per
-// compute unit.
+// The small-problem kernel, one tile per workgroup, 4 waves, K step 64, in two shapes.  A launch that
+// cannot fill the chip is bound by the latency of its loads, one K step after the other, so where 64 x 64
+// tiles still give every compute unit at most one workgroup they are used with eight stages (seven K steps
+// in flight, all of the unit's LDS): ViT-Large at micro-batch 1, 107 -> 65 us per layer.  Everything else
+// runs 128 x 128 tiles with two stages, two workgroups per compute unit (four stages and one workgroup per
+// unit were slower there: the second workgroup hides more than the deeper prefetch).
 hipError_t ep_bf16_gemm_small(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
                               void *C, int64_t M, int N, int K, int epi, hipStream_t s)
 {
@@ -276,6 +280,12 @@ hipError_t ep_bf16_gemm_small(const uint16_t *A, const uint16_t *W, const float 
     if (M * (int64_t)K * 2 >= 0x7FFFFFF0ll || (int64_t)N * K * 2 >= 0x7FFFFFF0ll || M * (int64_t)N >= (1ll << 31))
         return hipErrorInvalidValue;
     if (epi == EPI_BIAS_RESID && !resid) return hipErrorInvalidValue;
+    int cus = 0;
+    const hipError_t e = ep_device_cu_count(&cus);
+    if (e != hipSuccess) return e;
+    const int64_t t64 = ((M + 63) / 64) * ((N + 63) / 64);
+    if (t64 <= cus) return launch_epi<64, 64, 64, 8, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    if (t64 <= 2 * cus) return launch_epi<64, 64, 64, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     return launch_epi<128, 128, 64, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
 }
 
