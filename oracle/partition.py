@@ -1,6 +1,6 @@
 """Optimal pipeline partition by exhaustive enumeration (test infrastructure,
-not the product), plus the ctypes front end of the direct rendering of the
-paper's dynamic program in partition_oracle.c.
+not the product), plus the ctypes front end of the set-by-set evaluation of the
+paper's recurrence (Eq. 3) in partition_oracle.c.
 
 Problem (paper sections 3.2-3.3): choose S <= D distinct devices in an order
 and cut the L layers into S consecutive non-empty runs, stage k on device u_k.
@@ -116,10 +116,11 @@ def _clib():
 
 
 def paper_dp(t_comp, layer_mem, dev_mem, xfer_bytes, bw):
-    """T_opt and one optimal strategy from the three-dimensional DP h(i, S, u)
-    (Eq. 3, Algorithm 1).  Returns (None, None) if no strategy fits in memory.
-    Ties are broken by first discovery, so only T_opt and the validity of the
-    strategy are comparable with other solvers."""
+    """T_opt and one optimal strategy from the recurrence of Eq. 3 over (layers done,
+    device set, device of the last stage), evaluated set by set (partition_oracle.c).
+    Returns (None, None) if no strategy fits in memory.  Ties are broken by first
+    discovery, so only T_opt and the validity of the strategy are comparable with
+    other solvers."""
     t_comp = np.ascontiguousarray(t_comp, dtype=np.float64)
     L, D = t_comp.shape
     arrs = [np.ascontiguousarray(a, dtype=np.float64) for a in (layer_mem, dev_mem, xfer_bytes, bw)]
