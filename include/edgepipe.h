@@ -138,6 +138,11 @@ ep_status ep_stage_forward(ep_stage_t *stage, const void *x_in, int32_t B, void 
  * max_batch: B * T * (4*D + e*D + e*max(3*D, M)) bytes (e = 2 on the bf16 path,
  * 4 on the fp32 path; each part rounded up to 256) must fit, else UNSUPPORTED
  * with the two sizes in ep_last_error() (ViT-Huge bf16: B <= 14; ViT-Base: B <= 31).
+ * One exception to "bit for bit": at small micro-batches ep_stage_forward sums the
+ * second MLP layer over ranges of K and keeps the range sums in its workspace; where
+ * those do not fit next to the rest here, this call runs that layer uncut, and the
+ * results differ in the order of the fp32 additions over K (the range sums take at most
+ * 32 MiB, so never while the other intermediates stay under 32 MiB).
  * Every stage on a GPU shares that GPU's workspace and nothing in it is assumed
  * zero or kept between calls: calls that overlap in time on one GPU (two
  * streams, two threads) race; calls on one stream, or ordered by events, do not.

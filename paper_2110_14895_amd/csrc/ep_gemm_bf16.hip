@@ -79,7 +79,7 @@ __device__ inline int swz(int row)
 template <int BM, int BN, int BK_, int STAGES, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * BK_ * 2 <= 80 * 1024) ? 2 : 1) void gemm_bf16_kernel(
     const uint16_t *__restrict__ A, const uint16_t *__restrict__ W, const float *__restrict__ bias,
-    const float *resid, void *Cout, int M, int N, int K, int tiles_m, int tiles_n)
+    const float *resid, void *Cout, int M, int N, int K, int k_len, int tiles_m, int tiles_n)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int NW = WM * WN;                       // waves
@@ -96,11 +96,16 @@ __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * 
     uint4 *As = lds;
     uint4 *Ws = lds + STAGES * A_STAGE;
 
-    // ---- workgroup -> tile
-    const int total = tiles_m * tiles_n;
+    // ---- workgroup -> (K range, tile).  EPI_PARTIAL: K is cut into K / k_len ranges, range by range over
+    // all tiles (the workgroups of a range share W panels and sit on neighbouring ids of one XCD).
+    const int tiles = tiles_m * tiles_n;
+    const int total = EPI == EPI_PARTIAL ? tiles * (K / k_len) : tiles;
     const int per_xcd = (total + NUM_XCD - 1) / NUM_XCD;
-    const int lid = (int)(blockIdx.x % NUM_XCD) * per_xcd + (int)(blockIdx.x / NUM_XCD);
+    int lid = (int)(blockIdx.x % NUM_XCD) * per_xcd + (int)(blockIdx.x / NUM_XCD);
     if (lid >= total) return;
+    const int split = EPI == EPI_PARTIAL ? lid / tiles : 0;
+    lid -= split * tiles;
+    const int k0 = split * k_len;
     const int group_sz = GROUP_M * tiles_n;
     const int group = lid / group_sz;
     const int first_m = group * GROUP_M;
@@ -125,16 +130,16 @@ __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * 
         const int r = (i * NW + wave) * RPI + lane / CPR;
         const int c = (lane % CPR) ^ swz<BK_>(r);
         const int gr = m0 + r;
-        a_off[i] = gr < M ? (gr * K + c * 8) * 2 : 0x7FFFFFF0;     // beyond the buffer -> zeros
+        a_off[i] = gr < M ? (gr * K + k0 + c * 8) * 2 : 0x7FFFFFF0;     // beyond the buffer -> zeros
     }
 #pragma unroll
     for (int i = 0; i < W_LD; ++i) {
         const int r = (i * NW + wave) * RPI + lane / CPR;
         const int c = (lane % CPR) ^ swz<BK_>(r);
         const int gr = n0 + r;
-        w_off[i] = gr < N ? (gr * K + c * 8) * 2 : 0x7FFFFFF0;
+        w_off[i] = gr < N ? (gr * K + k0 + c * 8) * 2 : 0x7FFFFFF0;
     }
-    const int KT = K / BK_;
+    const int KT = k_len / BK_;
     auto issue = [&](int kt) {
         const int stage = kt % STAGES;
         // past the last K step the per-lane offset points beyond the buffer: zeros, no traffic (the
@@ -209,6 +214,11 @@ __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * 
             {
                 const int n = n0 + wn0 + ni * 16 + g4 * 4;
                 if (n >= N) continue;
+                if (EPI == EPI_PARTIAL) {          // the bare sum over this K range, fp32, range-major
+                    const float4 o = make_float4(acc[ni][mi][0], acc[ni][mi][1], acc[ni][mi][2], acc[ni][mi][3]);
+                    *reinterpret_cast<float4 *>(reinterpret_cast<float *>(Cout) + ((size_t)split * M + m) * N + n) = o;
+                    continue;
+                }
                 const float4 bb = *reinterpret_cast<const float4 *>(bias + n);
                 float v0 = acc[ni][mi][0] + bb.x;
                 float v1 = acc[ni][mi][1] + bb.y;
@@ -236,7 +246,7 @@ __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * 
 
 template <int BM, int BN, int BK_, int STAGES, int WM, int WN, int EPI>
 hipError_t launch_cfg(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
-                      void *C, int M, int N, int K, hipStream_t s)
+                      void *C, int M, int N, int K, int splits, hipStream_t s)
 {
     auto kern = gemm_bf16_kernel<BM, BN, BK_, STAGES, WM, WN, EPI>;
     constexpr size_t smem = (size_t)STAGES * (BM + BN) * (BK_ / 8) * sizeof(uint4);
@@ -244,9 +254,9 @@ hipError_t launch_cfg(const uint16_t *A, const uint16_t *W, const float *bias, c
     const hipError_t e = smem_limit.ensure(reinterpret_cast<const void *>(kern), (int)smem);
     if (e != hipSuccess) return e;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const int total = tiles_m * tiles_n;
+    const int total = tiles_m * tiles_n * splits;
     const int grid = (total + NUM_XCD - 1) / NUM_XCD * NUM_XCD;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, A, W, bias, resid, C, M, N, K,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), smem, s, A, W, bias, resid, C, M, N, K, K / splits,
                        tiles_m, tiles_n);
     return hipGetLastError();
 }
@@ -256,21 +266,22 @@ hipError_t launch_epi(const uint16_t *A, const uint16_t *W, const float *bias, c
                       void *C, int M, int N, int K, int epi, hipStream_t s)
 {
     switch (epi) {
-    case EPI_BIAS: return launch_cfg<BM, BN, BK_, STAGES, WM, WN, EPI_BIAS>(A, W, bias, resid, C, M, N, K, s);
-    case EPI_BIAS_GELU: return launch_cfg<BM, BN, BK_, STAGES, WM, WN, EPI_BIAS_GELU>(A, W, bias, resid, C, M, N, K, s);
-    case EPI_BIAS_RESID: return launch_cfg<BM, BN, BK_, STAGES, WM, WN, EPI_BIAS_RESID>(A, W, bias, resid, C, M, N, K, s);
+    case EPI_BIAS: return launch_cfg<BM, BN, BK_, STAGES, WM, WN, EPI_BIAS>(A, W, bias, resid, C, M, N, K, 1, s);
+    case EPI_BIAS_GELU: return launch_cfg<BM, BN, BK_, STAGES, WM, WN, EPI_BIAS_GELU>(A, W, bias, resid, C, M, N, K, 1, s);
+    case EPI_BIAS_RESID: return launch_cfg<BM, BN, BK_, STAGES, WM, WN, EPI_BIAS_RESID>(A, W, bias, resid, C, M, N, K, 1, s);
     }
     return hipErrorInvalidValue;
 }
 
 }  // namespace
 
-// The small-problem kernel, one tile per workgroup, 4 waves, K step 64, in two shapes.  A launch that
+// The small-problem kernel, one tile per workgroup, 4 waves, K step 64, in three shapes.  A launch that
 // cannot fill the chip is bound by the latency of its loads, one K step after the other, so where 64 x 64
 // tiles still give every compute unit at most one workgroup they are used with eight stages (seven K steps
-// in flight, all of the unit's LDS): ViT-Large at micro-batch 1, 107 -> 65 us per layer.  Everything else
-// runs 128 x 128 tiles with two stages, two workgroups per compute unit (four stages and one workgroup per
-// unit were slower there: the second workgroup hides more than the deeper prefetch).
+// in flight, all of the unit's LDS): ViT-Large at micro-batch 1, 107 -> 65 us per layer.  Up to two such
+// workgroups per compute unit: four stages each.  Everything else runs 128 x 128 tiles with two stages, two
+// workgroups per compute unit (four stages and one workgroup per unit were slower there: the second
+// workgroup hides more than the deeper prefetch).
 hipError_t ep_bf16_gemm_small(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
                               void *C, int64_t M, int N, int K, int epi, hipStream_t s)
 {
@@ -287,6 +298,29 @@ hipError_t ep_bf16_gemm_small(const uint16_t *A, const uint16_t *W, const float 
     if (t64 <= cus) return launch_epi<64, 64, 64, 8, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     if (t64 <= 2 * cus) return launch_epi<64, 64, 64, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     return launch_epi<128, 128, 64, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+}
+
+// The same kernel with K cut into `splits` ranges, one workgroup per (range, tile): part[r][m][n] is the
+// bare fp32 sum over range r.  For dense layers with few tiles and a long K (the second MLP layer at small
+// micro-batches: ViT-Large at micro-batch 1 is 64 tiles of 64 K steps), where the chain of K steps of a
+// single workgroup is the whole launch time.  Whoever consumes `part` adds the ranges in index order, so
+// the result does not depend on which workgroup finishes first.
+hipError_t ep_bf16_gemm_partial(const uint16_t *A, const uint16_t *W, float *part, int64_t M, int N, int K,
+                                int splits, hipStream_t s)
+{
+    if (M <= 0 || N <= 0) return hipSuccess;
+    if (splits < 1 || K <= 0 || K % (64 * splits) != 0 || N % 4 != 0) return hipErrorInvalidValue;
+    if (M * (int64_t)K * 2 >= 0x7FFFFFF0ll || (int64_t)N * K * 2 >= 0x7FFFFFF0ll || M * (int64_t)N >= (1ll << 31))
+        return hipErrorInvalidValue;
+    int cus = 0;
+    const hipError_t e = ep_device_cu_count(&cus);
+    if (e != hipSuccess) return e;
+    const int64_t w64 = ((M + 63) / 64) * ((N + 63) / 64) * splits;
+    if (w64 <= cus)
+        return launch_cfg<64, 64, 64, 8, 2, 2, EPI_PARTIAL>(A, W, nullptr, nullptr, part, (int)M, N, K, splits, s);
+    if (w64 <= 2 * cus)
+        return launch_cfg<64, 64, 64, 4, 2, 2, EPI_PARTIAL>(A, W, nullptr, nullptr, part, (int)M, N, K, splits, s);
+    return launch_cfg<128, 128, 64, 2, 2, 2, EPI_PARTIAL>(A, W, nullptr, nullptr, part, (int)M, N, K, splits, s);
 }
 
 namespace {
@@ -337,6 +371,43 @@ GemmPlan plan_gemm(int64_t M, int N, int K)
 }
 
 }  // namespace
+
+// Into how many K ranges a dense layer with fp32 output is cut (1: not at all).  Only problems that the
+// one-tile-per-workgroup kernel runs.  Such a launch is a chain of K steps per workgroup, and what a step costs
+// depends on the shape class the launch falls into (measured on ViT-Base/Large/Huge second MLP layers at
+// micro-batches 1 to 16, microseconds per 64-deep step): 64 x 64 tiles with one workgroup per compute unit 0.28,
+// with two 0.40; 128 x 128 tiles 0.7 while they leave compute units idle, 1.0 when they double up.  Cutting K
+// into sp ranges divides the chain by sp, may move the launch to a dearer class, and makes the consumer of the
+// sums read sp x M x N floats more (priced at 3 TB/s: they are spread over a few hundred waves).  The cheapest
+// sp of 1, 2, 4, 8 wins; every range keeps at least eight K steps and the workgroups at most two per compute unit.
+int ep_bf16_gemm_splits(int64_t M, int N, int K)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || K % 64 != 0) return 1;
+    if (plan_gemm(M, N, K).bn) return 1;
+    int cus = 0;
+    if (ep_device_cu_count(&cus) != hipSuccess) return 1;
+    const int64_t t64 = ((M + 63) / 64) * ((N + 63) / 64), t128 = ((M + 127) / 128) * ((N + 127) / 128);
+    const int steps = K / 64;
+    auto cost_us = [&](int sp) -> double {
+        double step;
+        if (t64 * sp <= cus) step = 0.28;
+        else if (t64 * sp <= 2 * cus) step = 0.40;
+        else if (t128 * sp <= cus) step = 0.7;
+        else if (t128 * sp <= 2 * cus) step = 1.0;
+        else step = 1.0 * (double)((t128 * sp + 2 * cus - 1) / (2 * cus));      // rounds of workgroups (sp == 1 only)
+        const double sums = sp > 1 ? (double)sp * (double)M * N * 4.0 / 3.0e6 : 0.0;
+        return (double)(steps / sp) * step + sums;
+    };
+    int best = 1;
+    double best_cost = cost_us(1);
+    for (int sp = 2; sp <= 8; sp *= 2) {
+        if (steps % sp != 0 || steps / sp < 8) break;
+        if ((t64 * sp <= 2 * cus ? t64 : t128) * sp > 2 * cus) break;
+        const double c = cost_us(sp);
+        if (c < best_cost - 1.0) { best = sp; best_cost = c; }      // a microsecond is within the noise of the model
+    }
+    return best;
+}
 
 int64_t ep_bf16_gemm_main_rows(int64_t M, int N, int K)
 {

@@ -9,6 +9,7 @@
 //   x    fp32 [R, D]            residual stream
 //   a    act  [R, D]            LayerNorm output, later the attention output
 //   big  act  [R, max(3D, M)]   q|k|v, later the MLP hidden activations
+//   part fp32 [S, R, D]         bf16 path, small R only: the second MLP layer's sums over S ranges of K
 // where act is bf16 on the bf16 path and fp32 on the fp32 path.
 #include <hip/hip_runtime.h>
 
@@ -47,6 +48,8 @@ struct Workspace {
     float *x;
     void *a;
     void *big;
+    float *part;
+    size_t part_bytes;
 };
 
 struct ep_stage {
@@ -58,7 +61,7 @@ struct ep_stage {
     size_t params_bytes = 0;
     char *ws = nullptr;
     size_t ws_bytes = 0;
-    Workspace own = {nullptr, nullptr, nullptr};   // inside ws
+    Workspace own = {nullptr, nullptr, nullptr, nullptr, 0};   // inside ws
     std::vector<LayerDev> layers;
     // per-kernel timing (ep_stage_trace_begin / _end)
     int trace_kernel = -1;
@@ -106,27 +109,41 @@ ep_status check_config(const ep_vit_config *c)
     return EP_OK;
 }
 
-// Workspace of a forward over `batch` images: x | a | big, each part 256-byte aligned.
-struct WorkspaceLayout { size_t x_bytes, a_bytes, big_bytes; };
+// K ranges of the second MLP layer at `batch` images (1: the layer runs uncut) and the bytes their sums take
+int fc2_splits(const ep_vit_config &c, int64_t batch)
+{
+    return c.param_dtype == EP_BF16 ? ep_bf16_gemm_splits(batch * c.n_tokens, c.d_model, c.d_mlp) : 1;
+}
 
-WorkspaceLayout workspace_layout(const ep_vit_config &c, int64_t batch)
+size_t part_bytes(const ep_vit_config &c, int64_t batch)
+{
+    const int sp = fc2_splits(c, batch);
+    return sp > 1 ? align_up((size_t)sp * batch * c.n_tokens * c.d_model * 4, 256) : 0;
+}
+
+// Workspace of a forward: x | a | big for `batch` images, then `part_b` bytes for the sums over K ranges;
+// each part 256-byte aligned.
+struct WorkspaceLayout { size_t x_bytes, a_bytes, big_bytes, part_b; };
+
+WorkspaceLayout workspace_layout(const ep_vit_config &c, int64_t batch, size_t part_b)
 {
     const size_t asz = c.param_dtype == EP_BF16 ? 2 : 4;     // bytes per activation-operand element
     const size_t R = (size_t)batch * c.n_tokens, D = c.d_model, M = c.d_mlp;
     const size_t wide = 3 * D > M ? 3 * D : M;
-    return {align_up(R * D * 4, 256), align_up(R * D * asz, 256), align_up(R * wide * asz, 256)};
+    return {align_up(R * D * 4, 256), align_up(R * D * asz, 256), align_up(R * wide * asz, 256), part_b};
 }
 
-size_t workspace_bytes(const ep_vit_config &c, int64_t batch)
+size_t workspace_bytes(const ep_vit_config &c, int64_t batch, size_t part_b)
 {
-    const WorkspaceLayout l = workspace_layout(c, batch);
-    return l.x_bytes + l.a_bytes + l.big_bytes;
+    const WorkspaceLayout l = workspace_layout(c, batch, part_b);
+    return l.x_bytes + l.a_bytes + l.big_bytes + l.part_b;
 }
 
-Workspace carve_workspace(char *base, const ep_vit_config &c, int64_t batch)
+Workspace carve_workspace(char *base, const ep_vit_config &c, int64_t batch, size_t part_b)
 {
-    const WorkspaceLayout l = workspace_layout(c, batch);
-    return {(float *)base, base + l.x_bytes, base + l.x_bytes + l.a_bytes};
+    const WorkspaceLayout l = workspace_layout(c, batch, part_b);
+    char *part = base + l.x_bytes + l.a_bytes + l.big_bytes;
+    return {(float *)base, base + l.x_bytes, base + l.x_bytes + l.a_bytes, part_b ? (float *)part : nullptr, part_b};
 }
 
 // Brackets one kernel of the layer with an event pair when that kernel is traced.  For a dense
@@ -155,17 +172,29 @@ struct TraceScope {
 // `call` may use ts_.after_main()
 #define EP_TRACED_GEMM(kernel, main_id, call) do { TraceScope ts_(st, kernel, main_id, s); EP_HIP(call); } while (0)
 
+// What a layer whose second MLP layer ran cut into K ranges has left for its successor: the residual stream
+// in w.x still lacks ((part[0] + ... + part[splits-1]) + bias).
+struct PendingSum { int splits; const float *bias; };
+
 // One layer on R = B*T rows.  `xin` is the residual stream read by this layer
 // (may be the caller's fp32 input), the layer leaves its result in `xout`.
+// `before`: the layer in front left its sums over K ranges in w.part (xin is w.x then); this layer's first
+// LayerNorm adds them.  `after`: if non-null the layer may leave its own in the same way (then xout must be
+// w.x, and *after says so with splits > 1); if null it finishes its output itself.
 ep_status run_layer(ep_stage *st, const Workspace &w, const LayerDev &L, const float *xin, float *xout, int B,
-                    hipStream_t s)
+                    hipStream_t s, const PendingSum *before, PendingSum *after)
 {
     const ep_vit_config &c = st->cfg;
     const int T = c.n_tokens, D = c.d_model, M = c.d_mlp, H = c.n_heads;
     const int64_t R = (int64_t)B * T;
+    if (after) *after = {1, nullptr};
     if (st->bf16) {
         uint16_t *a = (uint16_t *)w.a, *big = (uint16_t *)w.big;
-        EP_TRACED(EP_K_LN1, ep_bf16_layernorm(xin, L.ln1_g, L.ln1_b, c.ln_eps, a, R, D, s));
+        if (before && before->splits > 1)
+            EP_TRACED(EP_K_LN1, ep_bf16_layernorm_sum(w.x, w.part, before->splits, before->bias, L.ln1_g, L.ln1_b,
+                                                      c.ln_eps, a, R, D, s));
+        else
+            EP_TRACED(EP_K_LN1, ep_bf16_layernorm(xin, L.ln1_g, L.ln1_b, c.ln_eps, a, R, D, s));
         EP_TRACED_GEMM(EP_K_QKV, EP_K_QKV_MAIN,
                        ep_bf16_gemm(a, (const uint16_t *)L.w_qkv, L.b_qkv, nullptr, big, R, 3 * D, D, EPI_BIAS,
                                     ts_.after_main(), s));
@@ -177,9 +206,23 @@ ep_status run_layer(ep_stage *st, const Workspace &w, const LayerDev &L, const f
         EP_TRACED_GEMM(EP_K_FC1, EP_K_FC1_MAIN,
                        ep_bf16_gemm(a, (const uint16_t *)L.w_fc1, L.b_fc1, nullptr, big, R, M, D, EPI_BIAS_GELU,
                                     ts_.after_main(), s));
-        EP_TRACED_GEMM(EP_K_FC2, EP_K_FC2_MAIN,
-                       ep_bf16_gemm(big, (const uint16_t *)L.w_fc2, L.b_fc2, w.x, xout, R, D, M, EPI_BIAS_RESID,
-                                    ts_.after_main(), s));
+        int sp = w.part ? fc2_splits(c, B) : 1;
+        if ((size_t)sp * R * D * 4 > w.part_bytes) sp = 1;      // never beyond what the workspace holds
+        if (sp > 1) {
+            // few tiles and a long K: one workgroup per (K range, tile); the sums are added by the next
+            // layer's first LayerNorm, or here when nobody follows
+            TraceScope ts_(st, EP_K_FC2, EP_K_FC2_MAIN, s);
+            EP_HIP(ep_bf16_gemm_partial(big, (const uint16_t *)L.w_fc2, w.part, R, D, M, sp, s));
+            if (ts_.after_main()) EP_HIP(hipEventRecord(ts_.after_main(), s));
+            if (after && xout == w.x)
+                *after = {sp, L.b_fc2};
+            else
+                EP_HIP(ep_f32_residual_sum(w.x, w.part, sp, L.b_fc2, xout, R, D, s));
+        } else {
+            EP_TRACED_GEMM(EP_K_FC2, EP_K_FC2_MAIN,
+                           ep_bf16_gemm(big, (const uint16_t *)L.w_fc2, L.b_fc2, w.x, xout, R, D, M, EPI_BIAS_RESID,
+                                        ts_.after_main(), s));
+        }
     } else {
         float *a = (float *)w.a, *big = (float *)w.big;
         EP_TRACED(EP_K_LN1, ep_f32_layernorm(xin, L.ln1_g, L.ln1_b, c.ln_eps, a, R, D, s));
@@ -293,15 +336,21 @@ extern "C" ep_status ep_stage_create(const ep_vit_config *cfg, int32_t layer_beg
                             hipGetErrorString(e)));
     }
 
-    // ---- workspace
-    st->ws_bytes = workspace_bytes(st->cfg, max_batch);
+    // ---- workspace; the sums over K ranges only exist at small micro-batches (at most 2^15 rows), sized
+    // for the micro-batch that needs most
+    size_t part_max = 0;
+    for (int64_t b = 1; b <= max_batch && (b - 1) * T <= (1 << 15); ++b) {
+        const size_t pb = part_bytes(st->cfg, b);
+        if (pb > part_max) part_max = pb;
+    }
+    st->ws_bytes = workspace_bytes(st->cfg, max_batch, part_max);
     e = hipMalloc((void **)&st->ws, st->ws_bytes);
     if (e != hipSuccess) {
         st->ws = nullptr;
         return fail(ep_fail(EP_ERR_OOM, "hipMalloc of %zu workspace bytes failed: %s", st->ws_bytes,
                             hipGetErrorString(e)));
     }
-    st->own = carve_workspace(st->ws, st->cfg, max_batch);
+    st->own = carve_workspace(st->ws, st->cfg, max_batch, part_max);
 
     // ---- upload, one layer at a time through a host staging block
     std::vector<char> stage_buf;
@@ -357,10 +406,12 @@ ep_status forward_on(ep_stage *st, const Workspace &w, const void *x_in, int32_t
     } else {
         cur = (const float *)x_in;     // first layer reads the caller's buffer directly
     }
+    PendingSum pending = {1, nullptr};
     for (int l = 0; l < nl; ++l) {
         const bool last = l + 1 == nl;
         float *dst = (last && c.out_dtype == EP_F32) ? (float *)x_out : w.x;
-        ep_status rc = run_layer(st, w, st->layers[l], cur, dst, B, s);
+        const PendingSum before = pending;
+        ep_status rc = run_layer(st, w, st->layers[l], cur, dst, B, s, &before, last ? nullptr : &pending);
         if (rc != EP_OK) return rc;
         cur = dst;
     }
@@ -387,7 +438,11 @@ extern "C" ep_status ep_stage_forward_static(ep_stage_t *st, const void *x_in, i
 {
     if (!st || !x_in || !x_out) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_forward_static: null argument");
     if (B < 1) return ep_fail(EP_ERR_INVALID_ARG, "ep_stage_forward_static: B=%d, must be >= 1", B);
-    const size_t need = workspace_bytes(st->cfg, B);
+    // the sums over K ranges are an optimisation of small micro-batches: where they do not fit next to the rest,
+    // the second MLP layer runs uncut (same result up to the order of the fp32 additions over K)
+    const size_t need = workspace_bytes(st->cfg, B, 0);
+    size_t part_b = part_bytes(st->cfg, B);
+    if (need + part_b > (size_t)EP_STATIC_SCRATCH_BYTES) part_b = 0;
     if (need > (size_t)EP_STATIC_SCRATCH_BYTES)
         return ep_fail(EP_ERR_UNSUPPORTED,
                        "ep_stage_forward_static: a micro-batch of %d images needs %zu workspace bytes, the library's "
@@ -400,7 +455,7 @@ extern "C" ep_status ep_stage_forward_static(ep_stage_t *st, const void *x_in, i
     unsigned char *base = nullptr;
     const ep_status rc = static_scratch(dev, &base);      // looked up when the stage was created: a table read
     if (rc != EP_OK) return rc;
-    return forward_on(st, carve_workspace((char *)base, st->cfg, B), x_in, B, x_out, (hipStream_t)stream);
+    return forward_on(st, carve_workspace((char *)base, st->cfg, B, part_b), x_in, B, x_out, (hipStream_t)stream);
 }
 
 extern "C" ep_status ep_stage_profile(ep_stage_t *st, int32_t B, int32_t iters, void *stream,
@@ -429,11 +484,11 @@ extern "C" ep_status ep_stage_profile(ep_stage_t *st, int32_t B, int32_t iters, 
     for (int l = 0; l < nl && rc == EP_OK; ++l) {
         // fresh, bounded input for every layer so that repeated application cannot drift
         if ((e = ep_fill_pattern(st->own.x, n, s)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "fill failed: %s", hipGetErrorString(e)); break; }
-        rc = run_layer(st, st->own, st->layers[l], st->own.x, st->own.x, B, s);          // untimed
+        rc = run_layer(st, st->own, st->layers[l], st->own.x, st->own.x, B, s, nullptr, nullptr);          // untimed
         if (rc != EP_OK) break;
         if ((e = ep_fill_pattern(st->own.x, n, s)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "fill failed: %s", hipGetErrorString(e)); break; }
         if ((e = hipEventRecord(t0, s)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "hipEventRecord failed: %s", hipGetErrorString(e)); break; }
-        for (int it = 0; it < iters && rc == EP_OK; ++it) rc = run_layer(st, st->own, st->layers[l], st->own.x, st->own.x, B, s);
+        for (int it = 0; it < iters && rc == EP_OK; ++it) rc = run_layer(st, st->own, st->layers[l], st->own.x, st->own.x, B, s, nullptr, nullptr);
         if (rc != EP_OK) break;
         if ((e = hipEventRecord(t1, s)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "hipEventRecord failed: %s", hipGetErrorString(e)); break; }
         if ((e = hipEventSynchronize(t1)) != hipSuccess) { rc = ep_fail(EP_ERR_HIP, "hipEventSynchronize failed: %s", hipGetErrorString(e)); break; }

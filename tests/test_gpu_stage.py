@@ -157,6 +157,37 @@ def test_stage_composition_and_caller_stream():
     assert H.rel_err(ref, oracle.stage_forward(H.oracle_cfg(sh), layers, x)) <= H.TOL_BF16
 
 
+@pytest.mark.parametrize("T,D,Hh,M,B", [(50, 128, 2, 1024, 1), (197, 256, 4, 2048, 3), (65, 192, 3, 1536, 2)])
+def test_second_mlp_layer_cut_into_k_ranges(T, D, Hh, M, B):
+    # few output tiles and a long K: the second MLP layer runs as one workgroup per (K range, tile) and the
+    # next layer's first LayerNorm (or, after the last layer, a kernel of its own) adds the ranges.  The
+    # workspace of such a stage holds the range sums, which is how the test knows the path is taken.
+    import torch
+    sh = synth.custom_shape("bf_split", 3, D, Hh, M, T)
+    layers = layers_of(sh, 3, bf16=True, w_std=0.05)
+    x = synth.activations(sh, B, bf16=True)
+    whole = H.make_stage(sh, layers, 0, 3, B, bf16=True)
+    R = B * T
+    lean = R * D * 4 + R * D * 2 + R * max(3 * D, M) * 2               # x | a | big
+    params = 3 * (2 * (4 * D * D + 2 * D * M) + 4 * (9 * D + M))
+    assert whole.device_bytes() >= params + lean + 2 * R * D * 4, "no room for range sums: the path under test is not taken"
+    got = H.run_stage(whole, x)
+    ref = oracle.stage_forward(H.oracle_cfg(sh), layers, x)
+    e = H.rel_err(got, ref)
+    print(f"K ranges T={T} D={D} M={M} B={B}: err {e:.3e}")
+    assert e <= H.TOL_BF16
+    np.testing.assert_array_equal(H.run_stage(whole, x), got)             # same sums in the same order every time
+    # layer by layer through one-layer stages (each adds its own ranges) = the ranges added by the next LayerNorm
+    cur = x
+    for l in range(3):
+        st = H.make_stage(sh, layers[l:l + 1], l, l + 1, B, bf16=True, in_bf16=(l == 0))
+        cur = H.run_stage(st, cur)
+    np.testing.assert_array_equal(cur, got)
+    # bf16 output of the last layer: the fp32 result, rounded once
+    bf = H.run_stage(H.make_stage(sh, layers, 0, 3, B, bf16=True, out_bf16=True), x)
+    np.testing.assert_array_equal(bf, synth.round_to_bf16(got).reshape(got.shape))
+
+
 def test_determinism_and_workspace_poison():
     import torch
     sh = synth.custom_shape("bf_det", 2, 320, 4, 640, 257)

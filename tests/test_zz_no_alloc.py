@@ -52,7 +52,8 @@ def test_static_workspace_limit_is_enforced_at_the_real_width():
     for i in (0, 13):
         assert H.rel_err(got[i], oracle.stage_forward(H.oracle_cfg(sh), layers, x[i:i + 1])[0]) <= H.TOL_BF16
     # a smaller call after it, then one past the limit: refused, nothing launched, output untouched
-    np.testing.assert_array_equal(_run(lean.forward_static, lean.cfg, x[:3]), want[:3])
+    # (compared at its own size: a micro-batch of 3 takes the second MLP layer through another schedule than one of 14)
+    np.testing.assert_array_equal(_run(lean.forward_static, lean.cfg, x[:3]), _run(own.forward, own.cfg, x[:3]))
     big = torch.zeros((15,) + x.shape[1:], dtype=torch.int16, device="cuda")
     out = torch.full((15,) + x.shape[1:], 7.0, dtype=torch.float32, device="cuda")
     with pytest.raises(binding.EdgePipeError) as ei:
