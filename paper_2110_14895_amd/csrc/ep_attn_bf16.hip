@@ -345,16 +345,15 @@ __global__ __launch_bounds__((MAXQW + NLOADER) * 64) void attn_stream_kernel(con
     const int npass = (nqt + nqw - 1) / nqw;
 
     // Workgroup w sits on XCD w % 8 (round-robin dispatch).  Each XCD gets a contiguous range of
-    // (image, head) pairs, so that the heads of an image, which share cache lines of the qkv rows,
-    // meet in one L2; the workgroups of an XCD stride through it.
+    // (image, head) pairs, as long as its share of the workgroups, so that the heads of an image, which
+    // share cache lines of the qkv rows, meet in one L2; the workgroups of an XCD stride through it.
     int pair, pair_end, pair_step;
-    if (gridDim.x % 8 == 0) {
-        const int x = blockIdx.x % 8;
-        pair = (int)((int64_t)n_pairs * x / 8) + blockIdx.x / 8;
-        pair_end = (int)((int64_t)n_pairs * (x + 1) / 8);
-        pair_step = gridDim.x / 8;
-    } else {
-        pair = blockIdx.x; pair_end = n_pairs; pair_step = gridDim.x;
+    {
+        const int x = blockIdx.x % 8, g8 = gridDim.x / 8, r8 = gridDim.x % 8;
+        const int before = x * g8 + min(x, r8);                    // workgroups on the XCDs in front of this one
+        pair_step = g8 + (x < r8 ? 1 : 0);                         // workgroups on this one
+        pair = (int)((int64_t)n_pairs * before / gridDim.x) + blockIdx.x / 8;
+        pair_end = (int)((int64_t)n_pairs * (before + pair_step) / gridDim.x);
     }
     if (pair >= pair_end) return;                                  // whole workgroup
     const int my_pairs = (pair_end - pair + pair_step - 1) / pair_step;
@@ -466,8 +465,7 @@ hipError_t launch_stream(const uint16_t *qkv, uint16_t *o, int B, int T, int D, 
     int n_cu = 0;
     if ((e = ep_device_cu_count(&n_cu)) != hipSuccess) return e;
     const int n_pairs = B * H;
-    int grid = n_pairs < n_cu ? n_pairs : n_cu;
-    if (grid >= 8) grid -= grid % 8;       // a multiple of 8 keeps the XCD-contiguous pair ranges
+    const int grid = n_pairs < n_cu ? n_pairs : n_cu;      // one workgroup per compute unit, or per pair if there are fewer
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((nqw + NLOADER) * 64), S::smem, s, qkv, o, T, D, H, n_pairs,
                        scale_log2e);
     return hipGetLastError();

@@ -275,11 +275,13 @@ hipError_t launch_epi(const uint16_t *A, const uint16_t *W, const float *bias, c
 
 }  // namespace
 
-// The small-problem kernel, one tile per workgroup, 4 waves, K step 64, in three shapes.  A launch that
+// The small-problem kernel, one tile per workgroup, 4 waves, K step 64, in four shapes.  A launch that
 // cannot fill the chip is bound by the latency of its loads, one K step after the other, so where 64 x 64
 // tiles still give every compute unit at most one workgroup they are used with eight stages (seven K steps
 // in flight, all of the unit's LDS): ViT-Large at micro-batch 1, 107 -> 65 us per layer.  Up to two such
-// workgroups per compute unit: four stages each.  Everything else runs 128 x 128 tiles with two stages, two
+// workgroups per compute unit: four stages each.  Past that, 64 x 128 tiles with three stages while they
+// fit two per compute unit (128 x 128 tiles would leave a third of the units idle there: ViT-Large at
+// micro-batch 4, 80 -> 74 us per layer).  Everything else runs 128 x 128 tiles with two stages, two
 // workgroups per compute unit (four stages and one workgroup per unit were slower there: the second
 // workgroup hides more than the deeper prefetch).
 hipError_t ep_bf16_gemm_small(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
@@ -297,6 +299,8 @@ hipError_t ep_bf16_gemm_small(const uint16_t *A, const uint16_t *W, const float 
     const int64_t t64 = ((M + 63) / 64) * ((N + 63) / 64);
     if (t64 <= cus) return launch_epi<64, 64, 64, 8, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     if (t64 <= 2 * cus) return launch_epi<64, 64, 64, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
+    const int64_t t64x128 = ((M + 63) / 64) * ((N + 127) / 128);
+    if (t64x128 <= 2 * cus) return launch_epi<64, 128, 64, 3, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     return launch_epi<128, 128, 64, 2, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
 }
 
