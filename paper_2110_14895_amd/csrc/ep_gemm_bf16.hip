@@ -11,8 +11,8 @@
 // for the persistent kernel (ep_gemm_bf16_persist.hip) and the dispatcher
 // ep_bf16_gemm.
 //
-// Tiling.  A workgroup owns a BM x BN tile of C and walks K in steps of BK (64
-// or 32).  Each K step's A and W panels live in LDS as rows of 16-byte chunks;
+// Tiling.  A workgroup owns a BM x BN tile of C and walks K in steps of BK (128,
+// 64 or 32).  Each K step's A and W panels live in LDS as rows of 16-byte chunks;
 // chunk c of row r is stored at slot c ^ f(r) (f below), which makes the MFMA
 // fragment reads bank-conflict free without padding.  The panels go from global
 // memory straight into LDS (buffer_load ... lds), STAGES - 1 steps ahead of the
@@ -66,12 +66,13 @@ __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes
 #define EP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 
 // Row-dependent XOR applied to the 16-byte chunk index inside an LDS row, for
-// rows of 8 chunks (BK = 64) or 4 chunks (BK = 32).  Chosen so that the MFMA
-// fragment reads (32 consecutive rows, same logical chunk) spread over all
-// banks whether the LDS serves 8 or 16 lanes of a 128-bit read per cycle.
+// rows of 16 chunks (BK = 128), 8 chunks (BK = 64) or 4 chunks (BK = 32).  Chosen
+// so that the MFMA fragment reads (16 consecutive rows, same logical chunk) spread
+// over all banks whether the LDS serves 8 or 16 lanes of a 128-bit read per cycle.
 template <int BK_>
 __device__ inline int swz(int row)
 {
+    if (BK_ == 128) return row & 15;          // a row is 256 bytes, all the banks: 16 rows take 16 different chunks
     if (BK_ == 64) return (row & 7) ^ ((row >> 3) & 1);
     return ((row >> 1) & 3) ^ ((row >> 3) & 1);
 }
@@ -178,6 +179,27 @@ __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * 
         w_rd[kk] = (wn0 + l15) * CPR + ((kk * 4 + kc4) ^ fsw);
     }
 
+    // What the epilogue adds is fetched now, ahead of the first panel loads (loads return in order, so every
+    // counted wait below covers it): a small launch is a handful of K steps long and would otherwise end with
+    // one more trip to memory.  The residual only where it is a few registers (tiles of at most 64 rows).
+    constexpr bool PRE_RES = EPI == EPI_BIAS_RESID && MI * NI <= 8;
+    float4 bias_r[NI], res_r[PRE_RES ? NI : 1][PRE_RES ? MI : 1];
+    if (EPI != EPI_PARTIAL) {
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) {
+            const int n = n0 + wn0 + ni * 16 + g4 * 4;
+            bias_r[ni] = n < N ? *reinterpret_cast<const float4 *>(bias + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (PRE_RES) {
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    const int m = m0 + wm0 + mi * 16 + l15;
+                    res_r[ni][mi] = (m < M && n < N) ? *reinterpret_cast<const float4 *>(resid + (size_t)m * N + n)
+                                                     : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+        }
+    }
+
 #pragma unroll
     for (int st = 0; st < STAGES - 1; ++st) issue(st);
 
@@ -219,14 +241,15 @@ __global__ __launch_bounds__(WM *WN * 64, (WM * WN <= 4 && STAGES * (BM + BN) * 
                     *reinterpret_cast<float4 *>(reinterpret_cast<float *>(Cout) + ((size_t)split * M + m) * N + n) = o;
                     continue;
                 }
-                const float4 bb = *reinterpret_cast<const float4 *>(bias + n);
+                const float4 bb = bias_r[ni];
                 float v0 = acc[ni][mi][0] + bb.x;
                 float v1 = acc[ni][mi][1] + bb.y;
                 float v2 = acc[ni][mi][2] + bb.z;
                 float v3 = acc[ni][mi][3] + bb.w;
                 const size_t off = (size_t)m * N + n;
                 if (EPI == EPI_BIAS_RESID) {
-                    const float4 r = *reinterpret_cast<const float4 *>(resid + off);
+                    const float4 r = PRE_RES ? res_r[PRE_RES ? ni : 0][PRE_RES ? mi : 0]
+                                             : *reinterpret_cast<const float4 *>(resid + off);
                     float4 o = make_float4(v0 + r.x, v1 + r.y, v2 + r.z, v3 + r.w);
                     *reinterpret_cast<float4 *>(reinterpret_cast<float *>(Cout) + off) = o;
                 } else {
@@ -277,8 +300,10 @@ hipError_t launch_epi(const uint16_t *A, const uint16_t *W, const float *bias, c
 
 // The small-problem kernel, one tile per workgroup, 4 waves, K step 64, in four shapes.  A launch that
 // cannot fill the chip is bound by the latency of its loads, one K step after the other, so where 64 x 64
-// tiles still give every compute unit at most one workgroup they are used with eight stages (seven K steps
-// in flight, all of the unit's LDS): ViT-Large at micro-batch 1, 107 -> 65 us per layer.  Up to two such
+// tiles still give every compute unit at most one workgroup they are used with all of the unit's LDS in
+// flight: four stages of K steps of 128 (half the barriers of a step of 64: ViT-Large at micro-batch 1
+// 53.8 -> 50.2 us per layer), or eight stages of 64 when K is not a multiple of 128; ViT-Large at
+// micro-batch 1, 107 -> 65 us per layer against 128 x 128 tiles only.  Up to two such
 // workgroups per compute unit: four stages each.  Past that, 64 x 128 tiles with three stages while they
 // fit two per compute unit (128 x 128 tiles would leave a third of the units idle there: ViT-Large at
 // micro-batch 4, 80 -> 74 us per layer).  Everything else runs 128 x 128 tiles with two stages, two
@@ -297,6 +322,7 @@ hipError_t ep_bf16_gemm_small(const uint16_t *A, const uint16_t *W, const float 
     const hipError_t e = ep_device_cu_count(&cus);
     if (e != hipSuccess) return e;
     const int64_t t64 = ((M + 63) / 64) * ((N + 63) / 64);
+    if (t64 <= cus && K % 128 == 0) return launch_epi<64, 64, 128, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     if (t64 <= cus) return launch_epi<64, 64, 64, 8, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     if (t64 <= 2 * cus) return launch_epi<64, 64, 64, 4, 2, 2>(A, W, bias, resid, C, (int)M, N, K, epi, s);
     const int64_t t64x128 = ((M + 63) / 64) * ((N + 127) / 128);
@@ -320,6 +346,8 @@ hipError_t ep_bf16_gemm_partial(const uint16_t *A, const uint16_t *W, float *par
     const hipError_t e = ep_device_cu_count(&cus);
     if (e != hipSuccess) return e;
     const int64_t w64 = ((M + 63) / 64) * ((N + 63) / 64) * splits;
+    if (w64 <= cus && K % (128 * splits) == 0)
+        return launch_cfg<64, 64, 128, 4, 2, 2, EPI_PARTIAL>(A, W, nullptr, nullptr, part, (int)M, N, K, splits, s);
     if (w64 <= cus)
         return launch_cfg<64, 64, 64, 8, 2, 2, EPI_PARTIAL>(A, W, nullptr, nullptr, part, (int)M, N, K, splits, s);
     if (w64 <= 2 * cus)

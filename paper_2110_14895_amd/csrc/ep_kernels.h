@@ -52,7 +52,8 @@ bool ep_bf16_attention_supported(int T, int d_head);
 // deterministic fill used by the profiler (values in [-1, 1])
 hipError_t ep_fill_pattern(float *x, int64_t n, hipStream_t s);
 
-// one 128 x 128 tile per workgroup: problems too small for the persistent kernel
+// one tile per workgroup (64 x 64, 64 x 128 or 128 x 128 by the size of the problem): what is too small for the
+// persistent kernel
 hipError_t ep_bf16_gemm_small(const uint16_t *A, const uint16_t *W, const float *bias, const float *resid,
                               void *C, int64_t M, int N, int K, int epi, hipStream_t s);
 
