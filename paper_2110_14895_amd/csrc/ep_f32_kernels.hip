@@ -1,7 +1,7 @@
 // fp32 path of a ViT encoder layer (paper section 2.1): plain-ALU kernels used
 // for small fp32 configurations where exactness matters more than speed.
 // LayerNorm: one wavefront per row.  GEMM: 64x64 LDS tiles, 4x4 outputs per
-// thread.  Attention: one workgroup per (image, head, query), scores in LDS.
+// thread, the next K step's elements fetched while this one is multiplied.  Attention: one workgroup per (image, head, query), scores in LDS.
 #include "ep_kernels.h"
 
 namespace {
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(256) void ln_f32_kernel(const float *__restrict__ x
 
 // --------------------------------------------------------------------- GEMM
 constexpr int GT = 64;  // tile edge
-constexpr int GK = 16;  // k step
+constexpr int GK = 64;  // k step: few, long steps (each one costs a trip to memory on the small problems this path serves)
 
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__ A,
@@ -58,31 +58,44 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
                                                        const float *resid, float *C, int64_t M,
                                                        int N, int K)
 {
-    __shared__ float As[GK][GT + 1];
-    __shared__ float Ws[GK][GT + 1];
+    // rows padded to a multiple of 16 bytes: a thread's four a's (and w's) of one k are one 16-byte read
+    __shared__ __align__(16) float As[GK][GT + 4];
+    __shared__ __align__(16) float Ws[GK][GT + 4];
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
     const int64_t m0 = (int64_t)blockIdx.y * GT;
     const int n0 = blockIdx.x * GT;
     float acc[4][4] = {};
-    for (int k0 = 0; k0 < K; k0 += GK) {
-        // 64 rows x 16 k per operand = 1024 elements, 4 per thread
+    // 64 rows x GK k per operand, EPT elements per thread; the elements of step k0 + GK are fetched
+    // into registers while step k0 is multiplied out of LDS
+    constexpr int EPT = GT * GK / 256;
+    float ra[EPT], rw[EPT];
+    auto fetch = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < EPT; ++i) {
             const int id = threadIdx.x + i * 256;
-            const int r = id >> 4, k = id & 15;
+            const int r = id / GK, k = id % GK;
             const int64_t gm = m0 + r;
             const int gn = n0 + r;
-            As[k][r] = (gm < M && k0 + k < K) ? A[gm * K + k0 + k] : 0.f;
-            Ws[k][r] = (gn < N && k0 + k < K) ? W[(int64_t)gn * K + k0 + k] : 0.f;
+            ra[i] = (gm < M && k0 + k < K) ? A[gm * K + k0 + k] : 0.f;
+            rw[i] = (gn < N && k0 + k < K) ? W[(int64_t)gn * K + k0 + k] : 0.f;
+        }
+    };
+    fetch(0);
+    for (int k0 = 0; k0 < K; k0 += GK) {
+#pragma unroll
+        for (int i = 0; i < EPT; ++i) {
+            const int id = threadIdx.x + i * 256;
+            const int r = id / GK, k = id % GK;
+            As[k][r] = ra[i];
+            Ws[k][r] = rw[i];
         }
         __syncthreads();
+        if (k0 + GK < K) fetch(k0 + GK);
 #pragma unroll
         for (int k = 0; k < GK; ++k) {
-            float a[4], w[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = As[k][ty * 4 + i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) w[j] = Ws[k][tx * 4 + j];
+            const float4 a4 = *reinterpret_cast<const float4 *>(&As[k][ty * 4]);
+            const float4 w4 = *reinterpret_cast<const float4 *>(&Ws[k][tx * 4]);
+            const float a[4] = {a4.x, a4.y, a4.z, a4.w}, w[4] = {w4.x, w4.y, w4.z, w4.w};
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
