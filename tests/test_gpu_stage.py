@@ -204,10 +204,12 @@ def test_determinism_and_workspace_poison():
 def test_forward_under_graph_capture_replays_bit_exactly():
     # ep_stage_forward only enqueues kernels on the caller's stream (no allocation, no
     # synchronisation), so a caller may capture it in a graph: every replay, with eager work of
-    # the same stage in between, reproduces the eager result bit for bit.  Both dense-layer paths:
-    # persistent launches with a row remainder (ViT-Huge width, B = 16) and the small-tile kernel.
+    # the same stage in between, reproduces the eager result bit for bit.  All dense-layer paths:
+    # persistent launches with a row remainder (ViT-Huge width, B = 16), the small-tile kernel, and
+    # the second MLP layer cut into K ranges with the sums added by the next LayerNorm / the last kernel.
     import torch
     for sh, B in ((synth.custom_shape("bf_graph_small", 2, 320, 4, 640, 65), 3),
+                  (synth.custom_shape("bf_graph_ranges", 3, 256, 4, 2048, 197), 2),
                   (synth.custom_shape("bf_graph_wide", 1, 1280, 16, 5120, 257), 16)):
         layers = layers_of(sh, sh.n_layers, bf16=True, w_std=0.05)
         st = H.make_stage(sh, layers, 0, sh.n_layers, B, bf16=True)
